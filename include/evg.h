@@ -1,0 +1,196 @@
+/* evg.h -- C ABI of the EventGraD per-iteration parameter path on one MI355X.
+ *
+ * Scope.  The paper (arXiv 2103.07454) runs, on every worker ("PE") and every
+ * training iteration, after the local gradient is available (Algorithm B):
+ *   for every parameter tensor I:  if || xhat_I - x_I || >= delta_I  then send x_I
+ *   to both ring neighbours and set xhat_I := x_I          (Section 4, trigger cases)
+ *   delta_I := h * || xhat_I - x_I || / (k - khat)  at each event     (Section 4, Eq. 3)
+ *   x := average of own and the neighbours' last received values - lr * gradient
+ *                                                          (Section 3, Eq. 2; Section 4)
+ * optionally sending only the Top-K share of a tensor with its indices
+ * (Section 7).  This library runs that path for P ring workers simulated as P
+ * replicas resident in one GPU's memory: a "message" is a write into the
+ * neighbour's mailbox array (the paper's one-sided put into a window, Section 6).
+ *
+ * Conventions for every call
+ *   - returns an evg_status; never throws or aborts across the ABI; on failure
+ *     output arguments are left untouched and evg_error_text() explains.
+ *   - pointers are HOST pointers unless the comment says DEVICE.
+ *   - a context is bound to one HIP stream and is not re-entrant: calls on one
+ *     context must not overlap.  evg_step only enqueues work (no host sync).
+ */
+#ifndef EVG_H
+#define EVG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct evg_ctx evg_ctx;
+
+typedef enum {
+  EVG_OK = 0,
+  EVG_ERR_INVALID = 1, /* bad argument or configuration value            */
+  EVG_ERR_ALIGN = 2,   /* a device arena is not 16-byte aligned          */
+  EVG_ERR_OOM = 3,     /* device or host allocation failed               */
+  EVG_ERR_HIP = 4,     /* a HIP runtime call failed (no GPU, launch ...) */
+  EVG_ERR_STATE = 5    /* call order: iteration not increasing, ...      */
+} evg_status;
+
+enum { EVG_THR_FIXED = 0, EVG_THR_ADAPTIVE = 1 };
+enum { EVG_KEY_ABS_DRIFT = 0, EVG_KEY_ABS_VALUE = 1 };
+enum { EVG_GRAD_SYNTH = 0, EVG_GRAD_BUFFER = 1 };
+enum { EVG_DIST_NORMAL = 0, EVG_DIST_STUDENT_T3 = 1 };
+enum { EVG_NORM_FUSED = 0, EVG_NORM_SEPARATE = 1 };
+
+/* Synthetic gradients (they replace Algorithm B's "compute the local stochastic
+ * gradient"): element j of tensor l of worker r at iteration k is
+ * sigma_l(k) * z, z drawn from a Philox4x32-10 stream with key = seed and
+ * counter (j/4, l, k, r) for normals (four per block) or (j, l, k, r) for
+ * Student-t(3); sigma_l(k) = sigma0 [/ sqrt(fan_in_l)] * decay^k; with
+ * probability spike_prob a whole (worker, iteration) gradient is multiplied by
+ * spike_gain. */
+typedef struct {
+  uint64_t seed;
+  uint32_t dist;           /* EVG_DIST_*                                   */
+  uint32_t fan_in_scaling; /* nonzero: divide sigma0 by sqrt(fan_in)       */
+  double sigma0;           /* >= 0                                         */
+  double decay;            /* > 0                                          */
+  float spike_prob;        /* in [0, 1]                                    */
+  float spike_gain;
+} evg_synth;
+
+typedef struct {
+  uint32_t P;                   /* ring size, >= 3 (Section 3: two distinct neighbours) */
+  uint32_t L;                   /* parameter tensors per worker, >= 1                   */
+  const uint64_t* layer_numel;  /* [L], each 1 .. 2^31-8; read during evg_init only     */
+  const uint32_t* layer_fan_in; /* [L] or NULL when fan_in_scaling == 0                 */
+  float lr;                     /* step size gamma (Eq. 2)                              */
+  float momentum;               /* 0 = the paper's plain SGD                            */
+  uint32_t thr_mode;            /* EVG_THR_FIXED: delta = thr_fixed for every tensor;
+                                   EVG_THR_ADAPTIVE: Eq. 3                              */
+  float thr_fixed;              /* >= 0; 0 and +inf are legal                           */
+  float horizon;                /* h of Eq. 3 (1 in the paper's experiments)            */
+  uint32_t hist_len;            /* 1 = Eq. 3 as printed; up to 16 = mean of the slopes
+                                   between the last hist_len events (Section 7)        */
+  float delta_init;             /* adaptive threshold before a tensor's first event     */
+  uint32_t force_first;         /* nonzero: every tensor sends at iteration 0 (Section 4) */
+  uint32_t topk_ppm;            /* 0 = whole tensors; else K = max(1, ceil(n*ppm/1e6))
+                                   elements per event (Section 7); a tensor's first
+                                   event is always sent whole                           */
+  uint32_t topk_key;            /* EVG_KEY_*: rank by |x - xhat| or by |x|              */
+  uint32_t grad_mode;           /* EVG_GRAD_*                                           */
+  uint32_t norm_mode;           /* EVG_NORM_FUSED: the update pass also accumulates the
+                                   next iteration's drift norms; EVG_NORM_SEPARATE: a
+                                   pass of its own reads x and xhat                     */
+  uint32_t chunk_elems;         /* work granule: 0 (= 4096), 1024, 2048, 4096 or 8192   */
+  evg_synth synth;
+  /* DEVICE arenas owned by the caller, each P * evg_padded_numel() floats,
+   * 16-byte aligned, non-overlapping, alive until evg_destroy.  Worker r's
+   * tensor l starts at r * padded_numel + offset_l (evg_layer_offsets).  x holds
+   * the initial parameters at evg_init; the library then sets xhat := x and
+   * vel := 0 and treats both mailboxes as empty (their contents are never read
+   * before a first message arrives). */
+  float* x;      /* current parameters                                   */
+  float* xhat;   /* values last sent (Section 4, X-hat)                   */
+  float* mbox_l; /* last received from the left neighbour (r-1)           */
+  float* mbox_r; /* last received from the right neighbour (r+1)          */
+  float* vel;    /* momentum buffer                                       */
+} evg_config;
+
+/* Counters since evg_init (Section 7: share of messages, share of communication).
+ * One event = one (worker, tensor, iteration) that fired = two puts. */
+typedef struct {
+  uint64_t iters;           /* evg_step calls completed                          */
+  uint64_t events_total;    /* events_full + events_topk                         */
+  uint64_t events_full;     /* events that sent the whole tensor                 */
+  uint64_t events_topk;     /* events that sent a Top-K message                  */
+  uint64_t value_words;     /* parameter values sent, per event (not per put)    */
+  uint64_t index_words;     /* indices sent, per event                           */
+  uint64_t bytes_sent;      /* 4 * (value + index words) * 2 puts                */
+  uint64_t regular_events;  /* P * L * iters: what Algorithm A would send        */
+  uint64_t regular_words;   /* P * N * iters                                     */
+  uint64_t near_tie_flags;  /* tests with |norm - delta| < 1e-6 * delta          */
+  uint64_t nonfinite_norms; /* tests whose norm was NaN or infinite              */
+  /* optional per-(worker, tensor) outputs, HOST arrays of P*L entries or NULL  */
+  uint32_t* events_full_rl;
+  uint32_t* events_topk_rl;
+  float* last_norm;          /* norm used by the most recent test                */
+  float* delta;              /* current threshold                                */
+  int32_t* last_event_iter;  /* khat of Eq. 3; -1 = never sent                   */
+  uint8_t* valid_l;          /* has worker r received tensor l from the left ... */
+  uint8_t* valid_r;          /* ... from the right                               */
+} evg_stats_t;
+
+/* Phases reported by evg_timing_read. */
+enum {
+  EVG_PH_NORM = 0,       /* separate drift-norm pass (EVG_NORM_SEPARATE only)        */
+  EVG_PH_TRIGGER = 1,    /* norm finalisation, trigger test, thresholds, work lists  */
+  EVG_PH_SEND_FULL = 2,  /* whole-tensor copies into xhat and both mailboxes         */
+  EVG_PH_TOPK_SELECT = 3,/* threshold-key search for the Top-K set                   */
+  EVG_PH_TOPK_SEND = 4,  /* pack (index, value) messages, put them                   */
+  EVG_PH_UPDATE = 5,     /* fused averaging + momentum SGD (+ next drift norms)      */
+  EVG_PH_COUNT = 6
+};
+
+/* Size in floats of one worker's slice of an arena: every tensor start is
+ * padded to 4 elements and the slice to 64 elements.  0 on invalid input. */
+uint64_t evg_padded_numel(uint32_t L, const uint64_t* layer_numel);
+
+/* offsets_out[l] = start of tensor l inside a worker's slice, in floats. */
+evg_status evg_layer_offsets(uint32_t L, const uint64_t* layer_numel, uint64_t* offsets_out);
+
+/* Validates cfg, builds the device tables, initialises xhat, vel and the
+ * thresholds (Section 4: nothing has been sent yet, so xhat = x).  hip_stream
+ * is a hipStream_t (NULL = the default stream); all work of this context is
+ * enqueued on it.  Allocates library-owned device memory (tables, work lists,
+ * Top-K histograms and message staging). */
+evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream);
+
+/* One iteration k = iter of Algorithm B for all P workers: trigger tests, sends
+ * (visible to every worker's update of the same iteration), then the averaging
+ * and SGD update.  iter must be larger than the previous call's and below 2^31.
+ * grad: DEVICE array laid out like x, required iff grad_mode == EVG_GRAD_BUFFER,
+ * read during the step.  Asynchronous on the context's stream. */
+evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad);
+
+/* Waits for the stream, then fills *out (array members that are non-NULL too). */
+evg_status evg_stats(evg_ctx* c, evg_stats_t* out);
+
+/* Decisions of the most recent step, HOST arrays of P*L entries, any may be NULL:
+ * fired (0 = silent, 1 = whole tensor, 2 = Top-K message), near_tie (the 1e-6
+ * band), norm and the threshold the norm was compared with.  Waits for the stream. */
+evg_status evg_last_decisions(evg_ctx* c, uint8_t* fired, uint8_t* near_tie, float* norm,
+                              float* delta_before);
+
+/* The Top-K message worker r sent for tensor l in the most recent step: ascending
+ * element indices within the tensor and their values (Section 7: values + indices
+ * = 2K words).  *count = K, or 0 if (r, l) sent no Top-K message; at most cap
+ * entries are copied to the HOST arrays idx / val (either may be NULL). */
+evg_status evg_message(evg_ctx* c, uint32_t r, uint32_t l, uint32_t* idx, float* val,
+                       uint64_t cap, uint64_t* count);
+
+/* Final model: out[j] = mean over workers of x[r][j] (last line of Algorithm B).
+ * out: DEVICE array of evg_padded_numel floats.  Asynchronous on the stream. */
+evg_status evg_average(evg_ctx* c, float* out);
+
+/* Per-phase GPU time.  enable != 0 starts bracketing every phase of every later
+ * step with HIP events on the context's stream (and clears earlier samples);
+ * evg_timing_read waits for the stream and returns, per phase, the summed
+ * milliseconds and the number of samples since enabling. */
+evg_status evg_timing(evg_ctx* c, int enable);
+evg_status evg_timing_read(evg_ctx* c, double ms_out[EVG_PH_COUNT], uint64_t samples_out[EVG_PH_COUNT]);
+
+/* Frees library-owned memory.  The caller's arenas are untouched. */
+evg_status evg_destroy(evg_ctx* c);
+
+const char* evg_strerror(evg_status s);
+/* Text of the most recent failure on this thread ("" if none). */
+const char* evg_error_text(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EVG_H */

@@ -1,0 +1,540 @@
+// Host side of libevg: argument checking, table construction, the per-iteration
+// launch sequence and the counters.  See include/evg.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/evg.h"
+#include "evg_internal.h"
+
+using namespace evg;
+
+namespace {
+
+thread_local std::string g_err;
+
+evg_status fail(evg_status s, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return s;
+}
+
+#define HIP_TRY(expr)                                                                   \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess)                                                               \
+      return fail(e_ == hipErrorOutOfMemory ? EVG_ERR_OOM : EVG_ERR_HIP, "%s: %s", #expr, \
+                  hipGetErrorString(e_));                                               \
+  } while (0)
+
+inline uint64_t pad_to(uint64_t v, uint64_t m) { return (v + m - 1) / m * m; }
+
+struct TimerPair { hipEvent_t a, b; int phase; };
+
+}  // namespace
+
+struct evg_ctx {
+  evg_config cfg{};
+  hipStream_t stream = nullptr;
+  Tables t{};
+  uint32_t chunk_elems = 4096;
+  uint32_t work_grid = 1;
+  std::vector<uint64_t> numel;      // per tensor
+  std::vector<uint32_t> K;          // per tensor Top-K message length
+  std::vector<uint32_t> msg_off;
+  std::vector<void*> owned;         // device allocations to free
+  uint64_t N = 0;                   // unpadded elements per worker
+  uint64_t iters = 0;
+  int64_t last_iter = -1;
+  // timing
+  bool timing = false;
+  std::vector<TimerPair> pending;
+  std::vector<hipEvent_t> pool;
+  double ms[EVG_PH_COUNT] = {0};
+  uint64_t samples[EVG_PH_COUNT] = {0};
+
+  template <typename T>
+  evg_status dalloc(T** p, size_t count, bool zero) {
+    void* d = nullptr;
+    const size_t bytes = (count ? count : 1) * sizeof(T);
+    hipError_t e = hipMalloc(&d, bytes);
+    if (e != hipSuccess) return fail(EVG_ERR_OOM, "hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(e));
+    owned.push_back(d);
+    if (zero) HIP_TRY(hipMemsetAsync(d, 0, bytes, stream));
+    *p = static_cast<T*>(d);
+    return EVG_OK;
+  }
+
+  evg_status drain_timers() {
+    if (pending.empty()) return EVG_OK;
+    HIP_TRY(hipStreamSynchronize(stream));
+    for (const TimerPair& p : pending) {
+      float m = 0.f;
+      HIP_TRY(hipEventElapsedTime(&m, p.a, p.b));
+      ms[p.phase] += (double)m;
+      samples[p.phase] += 1;
+      pool.push_back(p.a);
+      pool.push_back(p.b);
+    }
+    pending.clear();
+    return EVG_OK;
+  }
+
+  evg_status mark(hipEvent_t* ev) {
+    if (pool.empty()) {
+      HIP_TRY(hipEventCreate(ev));
+    } else {
+      *ev = pool.back();
+      pool.pop_back();
+    }
+    HIP_TRY(hipEventRecord(*ev, stream));
+    return EVG_OK;
+  }
+};
+
+namespace {
+
+// Brackets one phase with events when timing is on.
+struct Phase {
+  evg_ctx* c;
+  int phase;
+  hipEvent_t a{};
+  evg_status st = EVG_OK;
+  Phase(evg_ctx* c_, int ph) : c(c_), phase(ph) {
+    if (c->timing) st = c->mark(&a);
+  }
+  evg_status end() {
+    if (!c->timing || st != EVG_OK) return st;
+    hipEvent_t b;
+    st = c->mark(&b);
+    if (st == EVG_OK) c->pending.push_back({a, b, phase});
+    return st;
+  }
+};
+
+evg_status check_layers(uint32_t L, const uint64_t* layer_numel) {
+  if (L < 1 || !layer_numel) return fail(EVG_ERR_INVALID, "need L >= 1 tensors and their sizes");
+  uint64_t total = 0;
+  for (uint32_t l = 0; l < L; ++l) {
+    if (layer_numel[l] < 1 || layer_numel[l] > 0x7FFFFFF8ull)
+      return fail(EVG_ERR_INVALID, "tensor %u has %llu elements (1 .. 2^31-8 allowed)", l,
+                  (unsigned long long)layer_numel[l]);
+    total += pad_to(layer_numel[l], 4);
+    if (total > 0xFFFFFF00ull) return fail(EVG_ERR_INVALID, "a worker's slice exceeds 2^32 floats");
+  }
+  return EVG_OK;
+}
+
+bool finite_f(float v) { return std::isfinite(v); }
+
+}  // namespace
+
+extern "C" {
+
+const char* evg_strerror(evg_status s) {
+  switch (s) {
+    case EVG_OK: return "ok";
+    case EVG_ERR_INVALID: return "invalid argument";
+    case EVG_ERR_ALIGN: return "misaligned device pointer";
+    case EVG_ERR_OOM: return "out of memory";
+    case EVG_ERR_HIP: return "HIP runtime error";
+    case EVG_ERR_STATE: return "call out of order";
+  }
+  return "unknown status";
+}
+
+const char* evg_error_text(void) { return g_err.c_str(); }
+
+uint64_t evg_padded_numel(uint32_t L, const uint64_t* layer_numel) {
+  if (check_layers(L, layer_numel) != EVG_OK) return 0;
+  uint64_t total = 0;
+  for (uint32_t l = 0; l < L; ++l) total += pad_to(layer_numel[l], 4);
+  return pad_to(total, 64);
+}
+
+evg_status evg_layer_offsets(uint32_t L, const uint64_t* layer_numel, uint64_t* offsets_out) {
+  if (!offsets_out) return fail(EVG_ERR_INVALID, "offsets_out is NULL");
+  evg_status st = check_layers(L, layer_numel);
+  if (st != EVG_OK) return st;
+  uint64_t total = 0;
+  for (uint32_t l = 0; l < L; ++l) {
+    offsets_out[l] = total;
+    total += pad_to(layer_numel[l], 4);
+  }
+  return EVG_OK;
+}
+
+evg_status evg_destroy(evg_ctx* c) {
+  if (!c) return EVG_OK;
+  (void)hipStreamSynchronize(c->stream);
+  for (void* p : c->owned) (void)hipFree(p);
+  for (const TimerPair& p : c->pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  for (hipEvent_t e : c->pool) (void)hipEventDestroy(e);
+  delete c;
+  return EVG_OK;
+}
+
+evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
+  if (!out || !cfg) return fail(EVG_ERR_INVALID, "out and cfg must be non-NULL");
+  evg_status st = check_layers(cfg->L, cfg->layer_numel);
+  if (st != EVG_OK) return st;
+  if (cfg->P < 3 || cfg->P > 65535)
+    return fail(EVG_ERR_INVALID, "ring size P = %u (3 .. 65535: a worker needs two distinct neighbours)", cfg->P);
+  if (!finite_f(cfg->lr) || !finite_f(cfg->momentum)) return fail(EVG_ERR_INVALID, "lr and momentum must be finite");
+  if (cfg->thr_mode > EVG_THR_ADAPTIVE) return fail(EVG_ERR_INVALID, "unknown thr_mode %u", cfg->thr_mode);
+  if (cfg->thr_mode == EVG_THR_FIXED && !(cfg->thr_fixed >= 0.0f))
+    return fail(EVG_ERR_INVALID, "thr_fixed must be >= 0 (+inf allowed)");
+  if (cfg->thr_mode == EVG_THR_ADAPTIVE) {
+    if (!finite_f(cfg->horizon) || cfg->horizon < 0.0f) return fail(EVG_ERR_INVALID, "horizon must be finite and >= 0");
+    if (!(cfg->delta_init >= 0.0f)) return fail(EVG_ERR_INVALID, "delta_init must be >= 0");
+    if (cfg->hist_len < 1 || cfg->hist_len > 16) return fail(EVG_ERR_INVALID, "hist_len must be 1 .. 16");
+  }
+  if (cfg->topk_ppm > 1000000u) return fail(EVG_ERR_INVALID, "topk_ppm must be <= 1000000");
+  if (cfg->topk_key > EVG_KEY_ABS_VALUE) return fail(EVG_ERR_INVALID, "unknown topk_key %u", cfg->topk_key);
+  if (cfg->grad_mode > EVG_GRAD_BUFFER) return fail(EVG_ERR_INVALID, "unknown grad_mode %u", cfg->grad_mode);
+  if (cfg->norm_mode > EVG_NORM_SEPARATE) return fail(EVG_ERR_INVALID, "unknown norm_mode %u", cfg->norm_mode);
+  const uint32_t ce = cfg->chunk_elems ? cfg->chunk_elems : 4096u;
+  if (ce != 1024 && ce != 2048 && ce != 4096 && ce != 8192)
+    return fail(EVG_ERR_INVALID, "chunk_elems must be 0, 1024, 2048, 4096 or 8192");
+  if (cfg->grad_mode == EVG_GRAD_SYNTH) {
+    const evg_synth& s = cfg->synth;
+    if (s.dist > EVG_DIST_STUDENT_T3) return fail(EVG_ERR_INVALID, "unknown synth.dist %u", s.dist);
+    if (!std::isfinite(s.sigma0) || s.sigma0 < 0) return fail(EVG_ERR_INVALID, "synth.sigma0 must be finite and >= 0");
+    if (!std::isfinite(s.decay) || s.decay <= 0) return fail(EVG_ERR_INVALID, "synth.decay must be finite and > 0");
+    if (!(s.spike_prob >= 0.0f && s.spike_prob <= 1.0f)) return fail(EVG_ERR_INVALID, "synth.spike_prob must be in [0,1]");
+    if (!finite_f(s.spike_gain)) return fail(EVG_ERR_INVALID, "synth.spike_gain must be finite");
+    if (s.fan_in_scaling) {
+      if (!cfg->layer_fan_in) return fail(EVG_ERR_INVALID, "fan_in_scaling needs layer_fan_in");
+      for (uint32_t l = 0; l < cfg->L; ++l)
+        if (cfg->layer_fan_in[l] < 1) return fail(EVG_ERR_INVALID, "layer_fan_in[%u] must be >= 1", l);
+    }
+  }
+  const uint64_t Npad = evg_padded_numel(cfg->L, cfg->layer_numel);
+  const uint64_t arena_bytes = (uint64_t)cfg->P * Npad * 4;
+  const float* arenas[5] = {cfg->x, cfg->xhat, cfg->mbox_l, cfg->mbox_r, cfg->vel};
+  static const char* names[5] = {"x", "xhat", "mbox_l", "mbox_r", "vel"};
+  for (int i = 0; i < 5; ++i) {
+    if (!arenas[i]) return fail(EVG_ERR_INVALID, "arena %s is NULL", names[i]);
+    if ((uintptr_t)arenas[i] % 16) return fail(EVG_ERR_ALIGN, "arena %s is not 16-byte aligned", names[i]);
+  }
+  for (int i = 0; i < 5; ++i)
+    for (int j = i + 1; j < 5; ++j) {
+      const uintptr_t a = (uintptr_t)arenas[i], b = (uintptr_t)arenas[j];
+      if (a < b + arena_bytes && b < a + arena_bytes)
+        return fail(EVG_ERR_INVALID, "arenas %s and %s overlap", names[i], names[j]);
+    }
+
+  // ---- host tables --------------------------------------------------------
+  evg_ctx* c = new (std::nothrow) evg_ctx();
+  if (!c) return fail(EVG_ERR_OOM, "host allocation failed");
+  c->cfg = *cfg;
+  c->cfg.layer_numel = nullptr;
+  c->cfg.layer_fan_in = nullptr;
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  c->chunk_elems = ce;
+  const uint32_t P = cfg->P, L = cfg->L;
+  std::vector<LayerDesc> layers(L);
+  std::vector<ChunkDesc> chunks;
+  uint64_t off = 0, ktot = 0;
+  for (uint32_t l = 0; l < L; ++l) {
+    const uint64_t n = cfg->layer_numel[l];
+    LayerDesc& d = layers[l];
+    d.off = (uint32_t)off;
+    d.numel = (uint32_t)n;
+    d.chunk0 = (uint32_t)chunks.size();
+    d.nchunks = (uint32_t)((n + ce - 1) / ce);
+    uint64_t k = 0;
+    if (cfg->topk_ppm) {
+      k = (n * (uint64_t)cfg->topk_ppm + 999999ull) / 1000000ull;
+      if (k < 1) k = 1;
+      if (k > n) k = n;
+    }
+    d.K = (uint32_t)k;
+    d.msg_off = (uint32_t)ktot;
+    ktot += k;
+    d.sig_base = cfg->synth.sigma0;
+    if (cfg->grad_mode == EVG_GRAD_SYNTH && cfg->synth.fan_in_scaling)
+      d.sig_base = cfg->synth.sigma0 / std::sqrt((double)cfg->layer_fan_in[l]);
+    for (uint32_t i = 0; i < d.nchunks; ++i) {
+      ChunkDesc cd;
+      cd.j0 = i * ce;
+      cd.off = d.off + cd.j0;
+      cd.len = (uint32_t)(n - cd.j0 < ce ? n - cd.j0 : ce);
+      cd.layer = l;
+      chunks.push_back(cd);
+    }
+    c->numel.push_back(n);
+    c->K.push_back(d.K);
+    c->msg_off.push_back(d.msg_off);
+    c->N += n;
+    off += pad_to(n, 4);
+  }
+  const uint64_t C = chunks.size();
+  if ((uint64_t)P * C > 0xFFFFFFF0ull || ktot > 0xFFFFFFF0ull) {
+    delete c;
+    return fail(EVG_ERR_INVALID, "too many chunks for 32-bit work lists");
+  }
+  const uint64_t S = (uint64_t)P * L;
+
+  // ---- device tables ------------------------------------------------------
+  Tables& t = c->t;
+  t.P = P; t.L = L; t.C = (uint32_t)C; t.S = (uint32_t)S;
+  t.hist_len = cfg->thr_mode == EVG_THR_ADAPTIVE ? cfg->hist_len : 1;
+  t.Ktot = (uint32_t)ktot;
+  t.Npad = Npad;
+  t.x = cfg->x; t.xhat = cfg->xhat; t.mbox_l = cfg->mbox_l; t.mbox_r = cfg->mbox_r; t.vel = cfg->vel;
+  int dev = 0, cus = 256;
+  ChunkDesc* d_chunks = nullptr;
+  LayerDesc* d_layers = nullptr;
+#define TRY_OR_FREE(expr)              \
+  do {                                 \
+    evg_status s_ = (expr);            \
+    if (s_ != EVG_OK) {                \
+      evg_destroy(c);                  \
+      return s_;                       \
+    }                                  \
+  } while (0)
+#define HIP_OR_FREE(expr)                                                            \
+  do {                                                                               \
+    hipError_t e_ = (expr);                                                          \
+    if (e_ != hipSuccess) {                                                          \
+      evg_destroy(c);                                                                \
+      return fail(EVG_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));              \
+    }                                                                                \
+  } while (0)
+  HIP_OR_FREE(hipGetDevice(&dev));
+  HIP_OR_FREE(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  const uint64_t full_grid = (uint64_t)P * C;
+  c->work_grid = (uint32_t)(full_grid < (uint64_t)cus * 8 ? full_grid : (uint64_t)cus * 8);
+  TRY_OR_FREE(c->dalloc(&d_chunks, C, false));
+  TRY_OR_FREE(c->dalloc(&d_layers, L, false));
+  HIP_OR_FREE(hipMemcpyAsync(d_chunks, chunks.data(), C * sizeof(ChunkDesc), hipMemcpyHostToDevice, c->stream));
+  HIP_OR_FREE(hipMemcpyAsync(d_layers, layers.data(), L * sizeof(LayerDesc), hipMemcpyHostToDevice, c->stream));
+  t.chunks = d_chunks;
+  t.layers = d_layers;
+  TRY_OR_FREE(c->dalloc(&t.partials, P * C, true));
+  TRY_OR_FREE(c->dalloc(&t.delta, S, false));
+  TRY_OR_FREE(c->dalloc(&t.last_norm, S, true));
+  TRY_OR_FREE(c->dalloc(&t.delta_before, S, true));
+  TRY_OR_FREE(c->dalloc(&t.last_event, S, false));
+  TRY_OR_FREE(c->dalloc(&t.valid_l, S, true));
+  TRY_OR_FREE(c->dalloc(&t.valid_r, S, true));
+  TRY_OR_FREE(c->dalloc(&t.fired, S, true));
+  TRY_OR_FREE(c->dalloc(&t.near_tie, S, true));
+  TRY_OR_FREE(c->dalloc(&t.ev_full, S, true));
+  TRY_OR_FREE(c->dalloc(&t.ev_topk, S, true));
+  TRY_OR_FREE(c->dalloc(&t.near_cnt, S, true));
+  TRY_OR_FREE(c->dalloc(&t.nonfinite_cnt, S, true));
+  TRY_OR_FREE(c->dalloc(&t.slope_hist, S * t.hist_len, true));
+  TRY_OR_FREE(c->dalloc(&t.slope_cnt, S, true));
+  TRY_OR_FREE(c->dalloc(&t.seg_woff_full, S, true));
+  TRY_OR_FREE(c->dalloc(&t.seg_woff_topk, S, true));
+  TRY_OR_FREE(c->dalloc(&t.counts, 4, true));
+  TRY_OR_FREE(c->dalloc(&t.work_full, P * C, true));
+  if (cfg->topk_ppm) {
+    TRY_OR_FREE(c->dalloc(&t.work_topk, P * C, true));
+    TRY_OR_FREE(c->dalloc(&t.hist, S * kHistBins, true));
+    TRY_OR_FREE(c->dalloc(&t.sel_prefix, S, true));
+    TRY_OR_FREE(c->dalloc(&t.sel_krem, S, true));
+    TRY_OR_FREE(c->dalloc(&t.chunk_cnt, P * C, true));
+    TRY_OR_FREE(c->dalloc(&t.chunk_before, P * C, true));
+    TRY_OR_FREE(c->dalloc(&t.chunk_out, P * C, true));
+    TRY_OR_FREE(c->dalloc(&t.msg_idx, (uint64_t)P * ktot, true));
+    TRY_OR_FREE(c->dalloc(&t.msg_val, (uint64_t)P * ktot, true));
+  } else {
+    t.work_topk = t.work_full;   // never listed: k_expand only writes it for Top-K events
+  }
+  // nothing sent yet: xhat = x, khat = -1, delta = its starting value, v = 0
+  const float d0 = cfg->thr_mode == EVG_THR_FIXED ? cfg->thr_fixed : cfg->delta_init;
+  std::vector<float> dinit(S, d0);
+  HIP_OR_FREE(hipMemcpyAsync(t.delta, dinit.data(), S * sizeof(float), hipMemcpyHostToDevice, c->stream));
+  HIP_OR_FREE(hipMemsetAsync(t.last_event, 0xFF, S * sizeof(int32_t), c->stream));
+  HIP_OR_FREE(hipMemcpyAsync(t.xhat, t.x, arena_bytes, hipMemcpyDeviceToDevice, c->stream));
+  HIP_OR_FREE(hipMemsetAsync(t.vel, 0, arena_bytes, c->stream));
+  HIP_OR_FREE(launch_norm(t, ce, c->stream));
+  HIP_OR_FREE(hipStreamSynchronize(c->stream));   // host staging buffers above go out of scope
+#undef TRY_OR_FREE
+#undef HIP_OR_FREE
+  *out = c;
+  return EVG_OK;
+}
+
+evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
+  if (!c) return fail(EVG_ERR_INVALID, "context is NULL");
+  if ((int64_t)iter <= c->last_iter || iter >= 0x7FFFFFFFull)
+    return fail(EVG_ERR_STATE, "iteration %llu does not follow %lld", (unsigned long long)iter,
+                (long long)c->last_iter);
+  const evg_config& g = c->cfg;
+  if (g.grad_mode == EVG_GRAD_BUFFER) {
+    if (!grad) return fail(EVG_ERR_INVALID, "grad_mode is EVG_GRAD_BUFFER but grad is NULL");
+    if ((uintptr_t)grad % 16) return fail(EVG_ERR_ALIGN, "grad is not 16-byte aligned");
+  }
+  StepArgs a{};
+  a.k = (uint32_t)iter;
+  a.lr = g.lr;
+  a.mu = g.momentum;
+  a.thr_mode = g.thr_mode;
+  a.horizon = g.horizon;
+  a.force_first = g.force_first ? 1u : 0u;
+  a.topk_on = g.topk_ppm ? 1u : 0u;
+  a.topk_key = g.topk_key;
+  a.key0 = (uint32_t)g.synth.seed;
+  a.key1 = (uint32_t)(g.synth.seed >> 32);
+  a.decay_pow = std::pow(g.synth.decay, (double)iter);
+  a.spike_prob = g.synth.spike_prob;
+  a.spike_gain = g.synth.spike_gain;
+  a.grad = grad;
+  const Tables& t = c->t;
+  const bool fused = g.norm_mode == EVG_NORM_FUSED;
+  if (c->timing && c->pending.size() > 4096) {
+    evg_status st = c->drain_timers();
+    if (st != EVG_OK) return st;
+  }
+  evg_status st;
+  if (!fused) {
+    Phase ph(c, EVG_PH_NORM);
+    HIP_TRY(launch_norm(t, c->chunk_elems, c->stream));
+    if ((st = ph.end()) != EVG_OK) return st;
+  }
+  {
+    Phase ph(c, EVG_PH_TRIGGER);
+    HIP_TRY(launch_trigger(t, a, c->stream));
+    HIP_TRY(launch_scan(t, c->stream));
+    HIP_TRY(launch_expand(t, c->stream));
+    if ((st = ph.end()) != EVG_OK) return st;
+  }
+  {
+    Phase ph(c, EVG_PH_SEND_FULL);
+    HIP_TRY(launch_copy(t, c->chunk_elems, c->work_grid, c->stream));
+    if ((st = ph.end()) != EVG_OK) return st;
+  }
+  if (a.topk_on) {
+    {
+      Phase ph(c, EVG_PH_TOPK_SELECT);
+      HIP_TRY(launch_topk_select(t, a, c->chunk_elems, c->work_grid, c->stream));
+      if ((st = ph.end()) != EVG_OK) return st;
+    }
+    {
+      Phase ph(c, EVG_PH_TOPK_SEND);
+      HIP_TRY(launch_topk_send(t, a, c->chunk_elems, c->work_grid, c->stream));
+      if ((st = ph.end()) != EVG_OK) return st;
+    }
+  }
+  {
+    Phase ph(c, EVG_PH_UPDATE);
+    HIP_TRY(launch_update(t, a, c->chunk_elems, g.synth.dist, g.grad_mode, fused, c->stream));
+    if ((st = ph.end()) != EVG_OK) return st;
+  }
+  c->last_iter = (int64_t)iter;
+  c->iters += 1;
+  return EVG_OK;
+}
+
+evg_status evg_stats(evg_ctx* c, evg_stats_t* out) {
+  if (!c || !out) return fail(EVG_ERR_INVALID, "context and out must be non-NULL");
+  const Tables& t = c->t;
+  const size_t S = t.S;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  std::vector<uint32_t> ef(S), et(S), nt(S), nf(S);
+  HIP_TRY(hipMemcpy(ef.data(), t.ev_full, S * 4, hipMemcpyDeviceToHost));
+  HIP_TRY(hipMemcpy(et.data(), t.ev_topk, S * 4, hipMemcpyDeviceToHost));
+  HIP_TRY(hipMemcpy(nt.data(), t.near_cnt, S * 4, hipMemcpyDeviceToHost));
+  HIP_TRY(hipMemcpy(nf.data(), t.nonfinite_cnt, S * 4, hipMemcpyDeviceToHost));
+  if (out->last_norm) HIP_TRY(hipMemcpy(out->last_norm, t.last_norm, S * 4, hipMemcpyDeviceToHost));
+  if (out->delta) HIP_TRY(hipMemcpy(out->delta, t.delta, S * 4, hipMemcpyDeviceToHost));
+  if (out->last_event_iter) HIP_TRY(hipMemcpy(out->last_event_iter, t.last_event, S * 4, hipMemcpyDeviceToHost));
+  if (out->valid_l) HIP_TRY(hipMemcpy(out->valid_l, t.valid_l, S, hipMemcpyDeviceToHost));
+  if (out->valid_r) HIP_TRY(hipMemcpy(out->valid_r, t.valid_r, S, hipMemcpyDeviceToHost));
+  if (out->events_full_rl) std::memcpy(out->events_full_rl, ef.data(), S * 4);
+  if (out->events_topk_rl) std::memcpy(out->events_topk_rl, et.data(), S * 4);
+  uint64_t e_full = 0, e_topk = 0, vw = 0, iw = 0, near = 0, nonf = 0;
+  for (uint32_t r = 0; r < t.P; ++r)
+    for (uint32_t l = 0; l < t.L; ++l) {
+      const size_t s = (size_t)r * t.L + l;
+      e_full += ef[s];
+      e_topk += et[s];
+      vw += (uint64_t)ef[s] * c->numel[l] + (uint64_t)et[s] * c->K[l];
+      iw += (uint64_t)et[s] * c->K[l];
+      near += nt[s];
+      nonf += nf[s];
+    }
+  out->iters = c->iters;
+  out->events_full = e_full;
+  out->events_topk = e_topk;
+  out->events_total = e_full + e_topk;
+  out->value_words = vw;
+  out->index_words = iw;
+  out->bytes_sent = 2ull * 4ull * (vw + iw);
+  out->regular_events = (uint64_t)t.P * t.L * c->iters;
+  out->regular_words = (uint64_t)t.P * c->N * c->iters;
+  out->near_tie_flags = near;
+  out->nonfinite_norms = nonf;
+  return EVG_OK;
+}
+
+evg_status evg_last_decisions(evg_ctx* c, uint8_t* fired, uint8_t* near_tie, float* norm, float* delta_before) {
+  if (!c) return fail(EVG_ERR_INVALID, "context is NULL");
+  const Tables& t = c->t;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  if (fired) HIP_TRY(hipMemcpy(fired, t.fired, t.S, hipMemcpyDeviceToHost));
+  if (near_tie) HIP_TRY(hipMemcpy(near_tie, t.near_tie, t.S, hipMemcpyDeviceToHost));
+  if (norm) HIP_TRY(hipMemcpy(norm, t.last_norm, t.S * 4, hipMemcpyDeviceToHost));
+  if (delta_before) HIP_TRY(hipMemcpy(delta_before, t.delta_before, t.S * 4, hipMemcpyDeviceToHost));
+  return EVG_OK;
+}
+
+evg_status evg_message(evg_ctx* c, uint32_t r, uint32_t l, uint32_t* idx, float* val, uint64_t cap,
+                       uint64_t* count) {
+  if (!c || !count) return fail(EVG_ERR_INVALID, "context and count must be non-NULL");
+  const Tables& t = c->t;
+  if (r >= t.P || l >= t.L) return fail(EVG_ERR_INVALID, "no worker %u / tensor %u", r, l);
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  uint8_t code = 0;
+  HIP_TRY(hipMemcpy(&code, t.fired + (size_t)r * t.L + l, 1, hipMemcpyDeviceToHost));
+  if (code != 2 || !c->cfg.topk_ppm) {
+    *count = 0;
+    return EVG_OK;
+  }
+  const uint64_t K = c->K[l], n = K < cap ? K : cap;
+  const size_t base = (size_t)r * t.Ktot + c->msg_off[l];
+  if (idx && n) HIP_TRY(hipMemcpy(idx, t.msg_idx + base, n * 4, hipMemcpyDeviceToHost));
+  if (val && n) HIP_TRY(hipMemcpy(val, t.msg_val + base, n * 4, hipMemcpyDeviceToHost));
+  *count = K;
+  return EVG_OK;
+}
+
+evg_status evg_average(evg_ctx* c, float* out) {
+  if (!c || !out) return fail(EVG_ERR_INVALID, "context and out must be non-NULL");
+  if ((uintptr_t)out % 16) return fail(EVG_ERR_ALIGN, "out is not 16-byte aligned");
+  HIP_TRY(launch_average(c->t, out, c->stream));
+  return EVG_OK;
+}
+
+evg_status evg_timing(evg_ctx* c, int enable) {
+  if (!c) return fail(EVG_ERR_INVALID, "context is NULL");
+  evg_status st = c->drain_timers();
+  if (st != EVG_OK) return st;
+  for (int i = 0; i < EVG_PH_COUNT; ++i) { c->ms[i] = 0; c->samples[i] = 0; }
+  c->timing = enable != 0;
+  return EVG_OK;
+}
+
+evg_status evg_timing_read(evg_ctx* c, double ms_out[EVG_PH_COUNT], uint64_t samples_out[EVG_PH_COUNT]) {
+  if (!c || !ms_out || !samples_out) return fail(EVG_ERR_INVALID, "NULL argument");
+  evg_status st = c->drain_timers();
+  if (st != EVG_OK) return st;
+  for (int i = 0; i < EVG_PH_COUNT; ++i) { ms_out[i] = c->ms[i]; samples_out[i] = c->samples[i]; }
+  return EVG_OK;
+}
+
+}  // extern "C"

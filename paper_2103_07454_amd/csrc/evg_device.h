@@ -1,0 +1,154 @@
+// Device-side helpers for the gfx950 kernels: fixed-order reductions and scans
+// over 64-lane wavefronts, and the counter-based gradient generator.
+#pragma once
+#include "evg_internal.h"
+
+namespace evg {
+
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+__device__ __forceinline__ uint32_t wave_id() { return threadIdx.x >> 6; }
+
+// Sum over the 64 lanes by xor butterflies: every lane ends with the same value,
+// and the association order is fixed, so results repeat bit for bit.
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Sum over a 256-thread workgroup; valid in every thread.  `ws` is 4 doubles of LDS.
+__device__ __forceinline__ double block_sum(double v, double* ws) {
+  v = wave_sum(v);
+  if (lane_id() == 0) ws[wave_id()] = v;
+  __syncthreads();
+  const double total = ((ws[0] + ws[1]) + ws[2]) + ws[3];
+  __syncthreads();
+  return total;
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+  const uint32_t lane = lane_id();
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t t = __shfl_up(v, o, 64);
+    if (lane >= (uint32_t)o) v += t;
+  }
+  return v;
+}
+
+// Exclusive prefix sum over the threads of a workgroup of W wavefronts (thread
+// order); *total receives the workgroup sum.  `ws` is W uint32 of LDS.
+template <int W>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* ws, uint32_t* total) {
+  const uint32_t incl = wave_incl_scan(v);
+  if (lane_id() == 63) ws[wave_id()] = incl;
+  __syncthreads();
+  uint32_t before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < W; ++w) {
+    const uint32_t s = ws[w];
+    if ((uint32_t)w < wave_id()) before += s;
+    all += s;
+  }
+  __syncthreads();
+  *total = all;
+  return before + incl - v;
+}
+
+// ----------------------------------------------------------------------------
+// Synthetic gradients.  Philox4x32-10 (Salmon et al., SC'11): ten rounds, each
+// two 32x32->64 multiplies by fixed odd constants followed by xors with the
+// neighbouring words and the round key; the key advances by Weyl constants.
+// ----------------------------------------------------------------------------
+struct Rand4 { uint32_t w[4]; };
+
+__device__ __forceinline__ Rand4 philox(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                        uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t y0 = hi1 ^ c1 ^ k0, y2 = hi0 ^ c3 ^ k1;
+    c0 = y0; c1 = lo1; c2 = y2; c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  Rand4 r;
+  r.w[0] = c0; r.w[1] = c1; r.w[2] = c2; r.w[3] = c3;
+  return r;
+}
+
+// Top 23 bits to a float in (0,1); exact.
+__device__ __forceinline__ float unit_open(uint32_t w) {
+  return ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f;
+}
+
+// log of a normal positive float with only + * / fma, so that it rounds the same
+// on any IEEE machine: split off the exponent, fold the mantissa into
+// (sqrt(1/2), sqrt(2)], then the odd series of 2 atanh((m-1)/(m+1)).
+__device__ __forceinline__ float ln_series(float u) {
+  const uint32_t b = __float_as_uint(u);
+  int e = (int)(b >> 23) - 127;
+  float m = __uint_as_float((b & 0x007FFFFFu) | 0x3F800000u);
+  if (m > 1.41421354f) { m = m * 0.5f; e += 1; }
+  const float t = m - 1.0f;
+  const float s = t / (2.0f + t);
+  const float w = s * s;
+  float p = __builtin_fmaf(w, 0.111111112f, 0.142857149f);
+  p = __builtin_fmaf(w, p, 0.2f);
+  p = __builtin_fmaf(w, p, 0.333333343f);
+  p = __builtin_fmaf(w, p, 1.0f);
+  const float lm = (s + s) * p;
+  return __builtin_fmaf((float)e, 0.693147182f, lm);
+}
+
+// (cos, sin)(2 pi u), u in [0,1): quarter turns split off exactly, Taylor series
+// on the remaining [-pi/4, pi/4].
+__device__ __forceinline__ void turn_cos_sin(float u, float& c, float& s) {
+  const float a = 4.0f * u;
+  const int qi = (int)(a + 0.5f);
+  const float r = a - (float)qi;
+  const float th = r * 1.57079637f;
+  const float q = th * th;
+  float sp = __builtin_fmaf(q, 2.75573192e-6f, -1.98412701e-4f);
+  sp = __builtin_fmaf(q, sp, 8.33333377e-3f);
+  sp = __builtin_fmaf(q, sp, -0.166666672f);
+  sp = __builtin_fmaf(q, sp, 1.0f);
+  const float sn = th * sp;
+  float cp = __builtin_fmaf(q, -2.75573188e-7f, 2.48015876e-5f);
+  cp = __builtin_fmaf(q, cp, -1.38888892e-3f);
+  cp = __builtin_fmaf(q, cp, 4.16666679e-2f);
+  cp = __builtin_fmaf(q, cp, -0.5f);
+  const float cs = __builtin_fmaf(q, cp, 1.0f);
+  const int quad = qi & 3;
+  c = quad == 0 ? cs : quad == 1 ? -sn : quad == 2 ? -cs : sn;
+  s = quad == 0 ? sn : quad == 1 ? cs : quad == 2 ? -sn : -cs;
+}
+
+// Box-Muller on words (0,1) and (2,3): radius from the first, angle from the second.
+__device__ __forceinline__ void normals4(const Rand4& r, float z[4]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const float ua = unit_open(r.w[2 * h]);
+    const float ub = unit_open(r.w[2 * h + 1]);
+    const float rad = __builtin_sqrtf(-2.0f * ln_series(ua));
+    float c, s;
+    turn_cos_sin(ub, c, s);
+    z[2 * h] = rad * c;
+    z[2 * h + 1] = rad * s;
+  }
+}
+
+// Student-t with 3 degrees of freedom from four normals.
+__device__ __forceinline__ float student_t3(const float z[4]) {
+  const float q = __builtin_fmaf(z[3], z[3], __builtin_fmaf(z[2], z[2], z[1] * z[1]));
+  return z[0] * __builtin_sqrtf(3.0f / q);
+}
+
+// Key that ranks elements for Top-K: the bit pattern of a non-negative float is
+// monotone in its value, so unsigned compares order magnitudes.
+__device__ __forceinline__ uint32_t rank_key(float xv, float hv, uint32_t by_value) {
+  return __float_as_uint(__builtin_fabsf(by_value ? xv : xv - hv));
+}
+
+}  // namespace evg

@@ -1,0 +1,86 @@
+// Internal types shared by the host side of libevg and its gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace evg {
+
+constexpr int kThreads = 256;          // 4 wavefronts of 64 lanes
+constexpr int kLaneElems = 4;          // one float4 per lane and sweep
+constexpr int kSweep = kThreads * kLaneElems;   // elements one workgroup covers per sweep
+constexpr int kHistBins = 2048;        // 11 key bits per selection pass (passes A, B); pass C uses 512
+
+// A chunk is a run of one tensor's elements that one workgroup handles; it never
+// straddles tensors, starts at a multiple of 4 elements and is at most chunk_elems long.
+struct ChunkDesc {
+  uint32_t off;    // start inside a worker's arena slice (floats, multiple of 4)
+  uint32_t len;    // elements (multiple of 4 except a tensor's last chunk)
+  uint32_t layer;  // tensor index
+  uint32_t j0;     // start inside the tensor (multiple of 4)
+};
+
+struct LayerDesc {
+  uint32_t off;      // start inside a worker's slice
+  uint32_t numel;
+  uint32_t chunk0;   // first chunk
+  uint32_t nchunks;
+  uint32_t K;        // Top-K message length (0 when Top-K is off)
+  uint32_t msg_off;  // start of this tensor's message slot inside a worker's staging slice
+  double sig_base;   // sigma0 [/ sqrt(fan_in)]
+};
+
+// Device pointers and sizes, passed to kernels by value.
+struct Tables {
+  const ChunkDesc* chunks;
+  const LayerDesc* layers;
+  float* x; float* xhat; float* mbox_l; float* mbox_r; float* vel;
+  double* partials;        // [P*C] sum of squared drift per chunk
+  float* delta; float* last_norm; float* delta_before;
+  int32_t* last_event;
+  uint8_t* valid_l; uint8_t* valid_r; uint8_t* fired; uint8_t* near_tie;
+  uint32_t* ev_full; uint32_t* ev_topk; uint32_t* near_cnt; uint32_t* nonfinite_cnt;
+  float* slope_hist; uint32_t* slope_cnt;   // [S*hist_len], [S]
+  uint32_t* seg_woff_full; uint32_t* seg_woff_topk;   // [S] exclusive scans
+  uint32_t* counts;        // [0] chunks to copy whole, [1] chunks of Top-K tensors, [2] Top-K tensors
+  uint32_t* work_full; uint32_t* work_topk;   // [P*C] compact chunk lists (r*C + c)
+  uint32_t* hist;          // [S*kHistBins]
+  uint32_t* sel_prefix; uint32_t* sel_krem;   // [S]
+  uint2* chunk_cnt;        // [P*C] (keys above threshold, keys equal) per chunk
+  uint2* chunk_before;     // [P*C] the same, summed over the tensor's earlier chunks
+  uint2* chunk_out;        // [P*C] (first message slot, winners) per chunk
+  uint32_t* msg_idx; float* msg_val;          // [P*Ktot]
+  uint32_t P, L, C, S;
+  uint32_t hist_len;
+  uint32_t Ktot;           // sum of K over tensors
+  uint64_t Npad;
+};
+
+struct StepArgs {
+  uint32_t k;
+  float lr, mu;
+  uint32_t thr_mode;
+  float horizon;
+  uint32_t force_first;
+  uint32_t topk_on;
+  uint32_t topk_key;
+  uint32_t key0, key1;
+  double decay_pow;        // decay^k
+  float spike_prob, spike_gain;
+  const float* grad;       // buffer mode only
+};
+
+// launchers (each enqueues on the stream and returns the launch status)
+hipError_t launch_norm(const Tables& t, uint32_t chunk_elems, hipStream_t s);
+hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t dist,
+                         uint32_t grad_mode, bool fused_norm, hipStream_t s);
+hipError_t launch_trigger(const Tables& t, const StepArgs& a, hipStream_t s);
+hipError_t launch_scan(const Tables& t, hipStream_t s);
+hipError_t launch_expand(const Tables& t, hipStream_t s);
+hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s);
+hipError_t launch_topk_select(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid,
+                              hipStream_t s);
+hipError_t launch_topk_send(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid,
+                            hipStream_t s);
+hipError_t launch_average(const Tables& t, float* out, hipStream_t s);
+
+}  // namespace evg

@@ -1,0 +1,159 @@
+// Trigger test and whole-tensor sends.
+//   k_trigger  one wavefront per (worker, tensor): finishes the drift norm from the
+//              per-chunk partial sums in a fixed order, applies the event condition
+//              || xhat - x || >= delta (Section 4), recomputes the adaptive threshold
+//              at events (Eq. 3), marks the neighbours' mailbox slots as filled.
+//   k_scan     exclusive prefix sums of the fired flags weighted by chunk counts.
+//   k_expand   writes the compact lists of chunks to copy / to Top-K select.
+//   k_copy     x -> xhat, left neighbour's right mailbox, right neighbour's left
+//              mailbox for every listed chunk: the stand-in for the one-sided puts of
+//              Section 6.
+#include "evg_device.h"
+
+namespace evg {
+
+__global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
+  const uint32_t seg = blockIdx.x * (kThreads / 64) + wave_id();
+  if (seg >= T.S) return;           // whole wavefront leaves; no workgroup barrier below
+  const uint32_t r = seg / T.L, l = seg % T.L;
+  const LayerDesc ld = T.layers[l];
+  const double* part = T.partials + (size_t)r * T.C + ld.chunk0;
+  double acc = 0.0;
+  for (uint32_t i = lane_id(); i < ld.nchunks; i += 64) acc += part[i];
+  acc = wave_sum(acc);
+  if (lane_id() != 0) return;
+
+  const float d = (float)sqrt(acc);
+  const float dl = T.delta[seg];
+  T.last_norm[seg] = d;
+  T.delta_before[seg] = dl;
+  if (!(__builtin_fabsf(d) <= 3.402823466e+38f)) T.nonfinite_cnt[seg] += 1;   // NaN or inf
+  const bool near = __builtin_fabsf(d - dl) < 1e-6f * dl;
+  T.near_tie[seg] = near ? 1 : 0;
+  if (near) T.near_cnt[seg] += 1;
+  const bool fire = (A.force_first && A.k == 0) || (d >= dl);   // NaN never fires
+  uint8_t code = 0;
+  if (fire) {
+    const int32_t khat = T.last_event[seg];
+    if (A.thr_mode == 1) {
+      const float slope = d / (float)((int32_t)A.k - khat);
+      if (T.hist_len <= 1) {
+        T.delta[seg] = A.horizon * slope;
+      } else {
+        // mean of the slopes between the last hist_len consecutive events (Section 7)
+        float* hs = T.slope_hist + (size_t)seg * T.hist_len;
+        uint32_t cnt = T.slope_cnt[seg];
+        if (cnt == T.hist_len) {
+          for (uint32_t i = 1; i < cnt; ++i) hs[i - 1] = hs[i];
+          cnt -= 1;
+        }
+        hs[cnt++] = slope;
+        T.slope_cnt[seg] = cnt;
+        float sum = 0.0f;
+        for (uint32_t i = 0; i < cnt; ++i) sum += hs[i];
+        T.delta[seg] = A.horizon * (sum / (float)cnt);
+      }
+    }
+    T.last_event[seg] = (int32_t)A.k;
+    // a tensor's first message has nothing to patch on the receiving side: send it whole
+    if (!A.topk_on || khat < 0) { code = 1; T.ev_full[seg] += 1; }
+    else { code = 2; T.ev_topk[seg] += 1; }
+    const uint32_t left = (r + T.P - 1) % T.P, right = (r + 1) % T.P;
+    T.valid_r[left * T.L + l] = 1;    // I am my left neighbour's right-hand source
+    T.valid_l[right * T.L + l] = 1;
+  }
+  T.fired[seg] = code;
+}
+
+// One workgroup of 1024 threads scans all P*L flags.
+__global__ __launch_bounds__(1024) void k_scan(Tables T) {
+  __shared__ uint32_t ws[16];
+  const uint32_t per = (T.S + 1023u) / 1024u;
+  const uint32_t lo = threadIdx.x * per;
+  const uint32_t hi = lo + per < T.S ? lo + per : T.S;
+  uint32_t nf = 0, nt = 0, ns = 0;
+  for (uint32_t s = lo; s < hi; ++s) {
+    const uint32_t f = T.fired[s], nc = T.layers[s % T.L].nchunks;
+    if (f == 1) nf += nc;
+    if (f == 2) { nt += nc; ns += 1; }
+  }
+  uint32_t tf, tt, ts;
+  uint32_t of = block_excl_scan<16>(nf, ws, &tf);
+  uint32_t ot = block_excl_scan<16>(nt, ws, &tt);
+  (void)block_excl_scan<16>(ns, ws, &ts);
+  for (uint32_t s = lo; s < hi; ++s) {
+    const uint32_t f = T.fired[s], nc = T.layers[s % T.L].nchunks;
+    T.seg_woff_full[s] = of;
+    T.seg_woff_topk[s] = ot;
+    if (f == 1) of += nc;
+    if (f == 2) ot += nc;
+  }
+  if (threadIdx.x == 0) { T.counts[0] = tf; T.counts[1] = tt; T.counts[2] = ts; }
+}
+
+__global__ __launch_bounds__(kThreads) void k_expand(Tables T) {
+  const uint32_t seg = blockIdx.x * (kThreads / 64) + wave_id();
+  if (seg >= T.S) return;
+  const uint32_t f = T.fired[seg];
+  if (f == 0) return;
+  const uint32_t r = seg / T.L;
+  const LayerDesc ld = T.layers[seg % T.L];
+  uint32_t* dst = f == 1 ? T.work_full + T.seg_woff_full[seg] : T.work_topk + T.seg_woff_topk[seg];
+  const uint32_t first = r * T.C + ld.chunk0;
+  for (uint32_t i = lane_id(); i < ld.nchunks; i += 64) dst[i] = first + i;
+}
+
+template <int SWEEPS>
+__global__ __launch_bounds__(kThreads) void k_copy(Tables T) {
+  const uint32_t n = T.counts[0];
+  for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
+    const uint32_t w = T.work_full[i];
+    const uint32_t r = w / T.C, c = w % T.C;
+    const ChunkDesc cd = T.chunks[c];
+    const uint32_t left = (r + T.P - 1) % T.P, right = (r + 1) % T.P;
+    const float* src = T.x + (size_t)r * T.Npad + cd.off;
+    float* d0 = T.xhat + (size_t)r * T.Npad + cd.off;
+    float* d1 = T.mbox_r + (size_t)left * T.Npad + cd.off;
+    float* d2 = T.mbox_l + (size_t)right * T.Npad + cd.off;
+#pragma unroll
+    for (int it = 0; it < SWEEPS; ++it) {
+      const uint32_t e = it * kSweep + threadIdx.x * kLaneElems;
+      if (e < cd.len) {
+        const float4 v = *reinterpret_cast<const float4*>(src + e);
+        *reinterpret_cast<float4*>(d0 + e) = v;
+        *reinterpret_cast<float4*>(d1 + e) = v;
+        *reinterpret_cast<float4*>(d2 + e) = v;
+      }
+    }
+  }
+}
+
+hipError_t launch_trigger(const Tables& t, const StepArgs& a, hipStream_t s) {
+  const uint32_t grid = (t.S + 3) / 4;
+  k_trigger<<<dim3(grid), dim3(kThreads), 0, s>>>(t, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_scan(const Tables& t, hipStream_t s) {
+  k_scan<<<dim3(1), dim3(1024), 0, s>>>(t);
+  return hipGetLastError();
+}
+
+hipError_t launch_expand(const Tables& t, hipStream_t s) {
+  const uint32_t grid = (t.S + 3) / 4;
+  k_expand<<<dim3(grid), dim3(kThreads), 0, s>>>(t);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s) {
+  switch (chunk_elems / kSweep) {
+    case 1: k_copy<1><<<dim3(grid), dim3(kThreads), 0, s>>>(t); break;
+    case 2: k_copy<2><<<dim3(grid), dim3(kThreads), 0, s>>>(t); break;
+    case 4: k_copy<4><<<dim3(grid), dim3(kThreads), 0, s>>>(t); break;
+    case 8: k_copy<8><<<dim3(grid), dim3(kThreads), 0, s>>>(t); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace evg

@@ -1,0 +1,249 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by
+element on the same seeded inputs.  Decisions, message counts and Top-K indices
+must be bit-exact (flagged near ties excepted); fp32 state within 1e-5 of the
+largest magnitude -- in practice the runs are expected to agree bit for bit."""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2103_07454_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+INF = float("inf")
+
+
+@pytest.fixture(scope="module")
+def evg():
+    from paper_2103_07454_amd import evg as m
+    m.lib()
+    return m
+
+
+def pair(evg, oracle_mod, w, x0=None, gpu=None, **over):
+    if x0 is None:
+        x0 = inputs.replicate(w.x0(), w.P)
+    ring = evg.Ring.from_workload(w, x0, mailbox_fill=float("nan"), **over, **(gpu or {}))
+    orc = oracle_mod.Oracle.from_workload(w, x0, **over)
+    return ring, orc
+
+
+def note(name, rep):
+    print(f"\n[{name}] bitwise={rep['bitwise']} rel={ {k: f'{v:.1e}' for k, v in rep['rel'].items()} } "
+          f"near-tie pairs={rep['near_tie_pairs']}", flush=True)
+
+
+# --------------------------------------------------------------------------
+# the gradient generator, bit for bit
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dist,n_big", [(0, 6_000_003), (1, 1_500_001)])
+def test_generator_bitwise(evg, oracle_mod, dist, n_big):
+    """lr = 1, mu = 0, x0 = 0, no communication  =>  x = -g exactly."""
+    tensors = [inputs.TensorSpec("a", (n_big,), 27, "weight"), inputs.TensorSpec("b", (1000,), 64, "weight"),
+               inputs.TensorSpec("c", (5,), 3, "bias")]
+    w = inputs.Workload("gen", 3, tensors, 3, lr=1.0, momentum=0.0, thr_mode=inputs.THR_FIXED, thr_fixed=INF,
+                        force_first=0, dist=dist, sigma0=0.7, fan_in_scaling=1, decay=0.9,
+                        spike_prob=0.4, spike_gain=5.0, seed=0xDEADBEEF12345)
+    x0 = np.zeros((w.P, w.N), np.float32)
+    ring = evg.Ring.from_workload(w, x0)
+    orc = oracle_mod.Oracle.from_workload(w, x0)
+    prev = np.zeros((w.P, w.N), np.float64)
+    off = np.concatenate([[0], np.cumsum(w.layer_numel.astype(np.int64))])
+    for k in range(2):
+        ring.step(k)
+        x = ring.state("x")
+        for r in range(w.P):
+            for l in range(w.L):
+                g = orc.grad_tensor(r, k, l)
+                # x_k = x_{k-1} - g, one rounding; at k = 0 exactly -g
+                want = (prev[r, off[l]:off[l + 1]] - g.astype(np.float64)).astype(np.float32)
+                assert np.array_equal(x[r, off[l]:off[l + 1]], want), (k, r, l)
+        prev = x.astype(np.float64)
+    assert ring.stats()["events_total"] == 0
+
+
+# --------------------------------------------------------------------------
+# limits and small cases, including ragged tails and several chunks
+# --------------------------------------------------------------------------
+RAGGED = [inputs.TensorSpec("w0", (4097,), 16, "weight"), inputs.TensorSpec("b0", (1,), 16, "bias"),
+          inputs.TensorSpec("w1", (9000,), 32, "weight"), inputs.TensorSpec("b1", (7,), 32, "bias"),
+          inputs.TensorSpec("w2", (1023,), 8, "weight"), inputs.TensorSpec("w3", (1024,), 8, "weight"),
+          inputs.TensorSpec("w4", (20481,), 64, "weight"), inputs.TensorSpec("b4", (2,), 64, "bias"),
+          inputs.TensorSpec("b5", (3,), 64, "bias")]
+
+
+def ragged(**kw):
+    base = inputs.Workload("ragged", 5, RAGGED, 40, sigma0=0.05, fan_in_scaling=1, decay=0.98, seed=77)
+    return base.scaled(**kw)
+
+
+@pytest.mark.parametrize("chunk", [1024, 2048, 4096, 8192])
+@pytest.mark.parametrize("mode", ["fixed", "adaptive", "topk", "topk_value_key", "student_spike"])
+def test_ragged_all_modes(evg, oracle_mod, mode, chunk):
+    kw = dict(fixed=dict(thr_mode=inputs.THR_FIXED, thr_fixed=6e-2), adaptive=dict(),
+              topk=dict(topk_ppm=100_000), topk_value_key=dict(topk_ppm=50_000),
+              student_spike=dict(dist=inputs.DIST_STUDENT_T3, spike_prob=0.2, spike_gain=5.0, topk_ppm=10_000))[mode]
+    w = ragged(**kw)
+    over = dict(topk_key=1) if mode == "topk_value_key" else {}
+    ring, orc = pair(evg, oracle_mod, w, gpu=dict(chunk_elems=chunk), **over)
+    from helpers import lockstep
+    rep = lockstep(ring, orc, w.iters, sample_messages=64)
+    note(f"ragged/{mode}/{chunk}", rep)
+    st = ring.stats()
+    assert 0 < st["events_total"] < st["regular_events"]
+    assert all(rep["bitwise"].values())
+
+
+def test_threshold_zero_and_infinity(evg, oracle_mod):
+    from helpers import lockstep
+    w = ragged(thr_mode=inputs.THR_FIXED, thr_fixed=0.0)
+    x0 = inputs.distinct_params(w.N, w.P, 5, 0.1)
+    ring, orc = pair(evg, oracle_mod, w, x0=x0)
+    rep = lockstep(ring, orc, 12)
+    assert ring.stats()["events_total"] == w.P * w.L * 12 and all(rep["bitwise"].values())
+    w = ragged(thr_mode=inputs.THR_FIXED, thr_fixed=INF, force_first=0)
+    ring, orc = pair(evg, oracle_mod, w, x0=x0)
+    rep = lockstep(ring, orc, 12)
+    assert ring.stats()["events_total"] == 0 and rep["bitwise"]["x"]
+    # mailboxes were pre-filled with NaN and never written: they must never have been read
+    assert np.isfinite(ring.state("x")).all()
+    assert np.isnan(ring.state("mbox_l")).all()
+
+
+def test_topk_everything_equals_full_send(evg):
+    w = ragged()
+    a = evg.Ring.from_workload(w)
+    b = evg.Ring.from_workload(w, topk_ppm=1_000_000)
+    for k in range(20):
+        a.step(k)
+        b.step(k)
+        assert np.array_equal(a.decisions()["fired"] > 0, b.decisions()["fired"] > 0)
+    for name in ("x", "xhat", "vel", "mbox_l", "mbox_r"):
+        assert np.array_equal(a.state(name), b.state(name))
+
+
+def test_topk_all_equal_keys_take_lowest_indices(evg, oracle_mod):
+    """Zero gradients: every drift key is 0, so the K winners are indices 0..K-1."""
+    w = ragged(topk_ppm=100_000, sigma0=0.0, thr_mode=inputs.THR_FIXED, thr_fixed=0.0)
+    ring = evg.Ring.from_workload(w)
+    ring.step(0)
+    ring.step(1)
+    for l, n in enumerate(w.layer_numel):
+        idx, _ = ring.message(2, l)
+        assert np.array_equal(idx, np.arange(oracle_mod.topk_count(n, 100_000), dtype=np.uint32))
+
+
+def test_buffer_gradients_and_history(evg, oracle_mod):
+    import torch
+    from helpers import lockstep
+    w = ragged(thr_mode=inputs.THR_ADAPTIVE, horizon=1.3)
+    ring, orc = pair(evg, oracle_mod, w, grad_mode=1, hist_len=3)
+    lay = ring.layout
+    cache = {}
+
+    def host(k):
+        cache[k] = inputs.random_grads(w.P, w.N, 900 + k, 0.01)
+        return cache[k]
+
+    def dev(k):
+        return torch.from_numpy(lay.pad(inputs.random_grads(w.P, w.N, 900 + k, 0.01))).cuda()
+
+    keep = []
+
+    def dev_keep(k):
+        keep.append(dev(k))
+        return keep[-1]
+
+    rep = lockstep(ring, orc, 30, grads=host, gpu_grads=dev_keep)
+    note("buffer/hist3", rep)
+    assert all(rep["bitwise"].values())
+
+
+def test_separate_norm_pass_matches_fused(evg):
+    w = ragged(topk_ppm=100_000)
+    a = evg.Ring.from_workload(w)
+    b = evg.Ring.from_workload(w, norm_mode=evg.NORM_SEPARATE)
+    for k in range(25):
+        a.step(k)
+        b.step(k)
+        da, db = a.decisions(), b.decisions()
+        assert np.array_equal(da["fired"], db["fired"]) and np.array_equal(da["norm"], db["norm"])
+    assert np.array_equal(a.state("x"), b.state("x"))
+
+
+def test_determinism_across_runs_and_chunkings(evg):
+    w = ragged(topk_ppm=100_000)
+    runs = []
+    for chunk in (4096, 4096, 1024):
+        ring = evg.Ring.from_workload(w, chunk_elems=chunk)
+        fired = []
+        for k in range(30):
+            ring.step(k)
+            fired.append(ring.decisions()["fired"].copy())
+        runs.append((np.stack(fired), ring.state("x"), ring.state("xhat")))
+    assert all(np.array_equal(a, b) for a, b in zip(runs[0], runs[1]))      # bitwise repeatable
+    assert np.array_equal(runs[0][0], runs[2][0])                            # decisions survive re-chunking
+
+
+def test_final_average(evg, oracle_mod):
+    w = ragged()
+    ring, orc = pair(evg, oracle_mod, w)
+    for k in range(5):
+        ring.step(k)
+        orc.step(k)
+    assert np.array_equal(ring.average(), orc.average())
+
+
+def test_api_errors_on_device(evg):
+    w = ragged()
+    ring = evg.Ring.from_workload(w)
+    ring.step(3)
+    with pytest.raises(evg.EvgError) as e:
+        ring.step(3)
+    assert e.value.status == 5
+    with pytest.raises(evg.EvgError):
+        evg.Ring.from_workload(w.scaled(P=2), x0=np.zeros((2, w.N), np.float32))
+    ring = evg.Ring.from_workload(w, grad_mode=1)
+    with pytest.raises(evg.EvgError):
+        ring.step(0)
+
+
+# --------------------------------------------------------------------------
+# the benchmark configurations
+# --------------------------------------------------------------------------
+def test_config1_full_run(evg, oracle_mod):
+    from helpers import lockstep
+    w = inputs.config(1)
+    ring, orc = pair(evg, oracle_mod, w)
+    rep = lockstep(ring, orc, w.iters)
+    note(w.name, rep)
+    st = ring.stats()
+    print(f"  messages {100 * st['events_total'] / st['regular_events']:.1f}% of regular")
+    assert all(rep["bitwise"].values())
+
+
+def test_config2_full_run(evg, oracle_mod):
+    from helpers import lockstep
+    w = inputs.config(2)
+    ring, orc = pair(evg, oracle_mod, w)
+    rep = lockstep(ring, orc, w.iters, progress=100)
+    note(w.name, rep)
+    st = ring.stats()
+    print(f"  messages {100 * st['events_total'] / st['regular_events']:.1f}% of regular")
+    assert rep["rel"]["x"] <= 1e-5
+
+
+@pytest.mark.parametrize("i", [3, 4, 5])
+def test_reduced_width_configs_full_length(evg, oracle_mod, i):
+    """Configurations 3-5 with narrow channels: same tensor count, ring size, trigger
+    and send mode, full iteration count."""
+    from helpers import lockstep
+    w = inputs.reduced(i)
+    ring, orc = pair(evg, oracle_mod, w)
+    rep = lockstep(ring, orc, w.iters, sample_messages=16, progress=50)
+    note(w.name, rep)
+    st = ring.stats()
+    print(f"  messages {100 * st['events_total'] / st['regular_events']:.1f}% of regular, "
+          f"communication {100 * (st['value_words'] + st['index_words']) / st['regular_words']:.1f}%")
+    assert rep["rel"]["x"] <= 1e-5
