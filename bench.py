@@ -1,0 +1,141 @@
+#!/usr/bin/env python3
+"""Benchmark of the EventGraD per-iteration parameter path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5]
+
+One "step" is one evg_step: trigger tests, sends (whole tensors or Top-K
+messages) and the fused averaging + SGD update for all P simulated workers.
+The default workload is configuration 5 (P = 64 ring workers, ResNet-18-shaped
+parameter list, adaptive thresholds, Top-K 10 %, 100 iterations).  W warm-up
+steps run first; the state is then re-initialised (untimed) and K steps,
+iterations 0..K-1 of the configuration, are timed with inputs resident in HBM.
+
+Prints one JSON line: throughput in parameter-elements/s, the roofline figures
+of the dominant kernel (the fused update pass, timed with HIP events on the
+stream it runs on) and the CPU oracle's throughput on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published peak, GB/s
+UPDATE_BYTES_PER_ELEM = 28     # reads x, mbox_l, mbox_r, vel, xhat; writes x, vel (fp32)
+
+# HBM traffic of one k_update launch on configuration 5, measured with
+# rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of
+# known size); see profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def cpu_baseline(inputs, w, seconds_hint=20.0):
+    """The oracle as it stands, single thread, on a bounded sample of the same
+    workload: fewer ring workers, first iterations."""
+    import oracle
+    P, iters = 4, 5
+    ws = w.scaled(P=P)
+    x0 = inputs.replicate(ws.x0(), P)
+    orc = oracle.Oracle.from_workload(ws, x0)
+    t0 = time.perf_counter()
+    for k in range(iters):
+        orc.step(k)
+    dt = time.perf_counter() - t0
+    return {"value": P * ws.N * iters / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
+            "sample": f"{w.name} with P={P} ring workers, iterations 0..{iters - 1}, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5)
+    ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-phase-timers", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the parameter path of all P simulated workers on ONE GPU; "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2103_07454_amd import evg, inputs
+
+    w = inputs.config(args.config)
+    x0 = w.x0()[None, :]                       # common start; uploaded once per worker slice
+    x0 = np.broadcast_to(x0, (w.P, w.N))
+
+    def make():
+        return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk)
+
+    ring = make()
+    for k in range(args.warmup):
+        ring.step(k)
+    ring.synchronize()
+    ring.close()
+    del ring
+    torch.cuda.empty_cache()
+
+    ring = make()                              # fresh state: timed steps are iterations 0..K-1
+    if not args.no_phase_timers:
+        ring.timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ring.step(k)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    st = ring.stats(arrays=True)
+    phases = ring.timing_read() if not args.no_phase_timers else {}
+    elems = w.P * w.N
+    numel = w.layer_numel.astype(np.float64)
+    rho = w.topk_ppm / 1e6
+    f_full = float((st["events_full_rl"].astype(np.float64) * numel[None, :]).sum() / (elems * args.steps))
+    f_topk = float((st["events_topk_rl"].astype(np.float64) * numel[None, :]).sum() / (elems * args.steps))
+    step_bytes_per_elem = 28 + 16 * f_full + 8 * f_topk + 28 * rho * f_topk
+    out = {
+        "metric": "param_elements_per_s_fused_trigger_consensus_update",
+        "value": elems * args.steps / dt,
+        "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * dt / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
+                   "threshold": "adaptive" if w.thr_mode else "fixed", "topk_ppm": w.topk_ppm,
+                   "chunk_elems": args.chunk or 4096,
+                   "fraction_fired_full": f_full, "fraction_fired_topk": f_topk,
+                   "messages_pct_of_regular": 100.0 * st["events_total"] / max(1, st["regular_events"]),
+                   "communication_pct_of_regular":
+                       100.0 * (st["value_words"] + st["index_words"]) / max(1, st["regular_words"])},
+        "step_algorithmic_bytes_per_element": step_bytes_per_elem,
+        "step_achieved_GBps": step_bytes_per_elem * elems * args.steps / dt / 1e9,
+        "step_frac_of_hbm_peak": step_bytes_per_elem * elems * args.steps / dt / 1e9 / HBM_PEAK_GBS,
+    }
+    if phases:
+        ms_upd, n_upd = phases["update"]
+        avg_ms = ms_upd / max(1, n_upd)
+        achieved = UPDATE_BYTES_PER_ELEM * elems / (avg_ms * 1e-3) / 1e9
+        out["roofline"] = {"kernel": "k_update", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                           "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                           "avg_launch_ms": avg_ms, "launches": n_upd,
+                           "algorithmic_bytes_per_launch": UPDATE_BYTES_PER_ELEM * elems}
+        out["phase_ms_per_step"] = {p: ms / max(1, args.steps) for p, (ms, n) in phases.items()}
+    ring.close()
+    del ring
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inputs, w)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -8,6 +8,19 @@ namespace evg {
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
 __device__ __forceinline__ uint32_t wave_id() { return threadIdx.x >> 6; }
 
+// Streaming (non-temporal) 16-byte accesses: every arena is far larger than the
+// caches and is touched once per pass, so lines are not worth keeping.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld4s(const float* p) {
+  const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st4s(float* p, float4 a) {
+  f32x4 v;
+  v.x = a.x; v.y = a.y; v.z = a.z; v.w = a.w;
+  __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
+}
+
 // Sum over the 64 lanes by xor butterflies: every lane ends with the same value,
 // and the association order is fixed, so results repeat bit for bit.
 __device__ __forceinline__ double wave_sum(double v) {

@@ -119,10 +119,10 @@ __global__ __launch_bounds__(kThreads) void k_copy(Tables T) {
     for (int it = 0; it < SWEEPS; ++it) {
       const uint32_t e = it * kSweep + threadIdx.x * kLaneElems;
       if (e < cd.len) {
-        const float4 v = *reinterpret_cast<const float4*>(src + e);
-        *reinterpret_cast<float4*>(d0 + e) = v;
-        *reinterpret_cast<float4*>(d1 + e) = v;
-        *reinterpret_cast<float4*>(d2 + e) = v;
+        const float4 v = ld4s(src + e);
+        st4s(d0 + e, v);
+        st4s(d1 + e, v);
+        st4s(d2 + e, v);
       }
     }
   }

@@ -9,8 +9,8 @@
 
 namespace evg {
 
-__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
-__device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ float4 ld4(const float* p) { return ld4s(p); }
+__device__ __forceinline__ void st4(float* p, float4 v) { st4s(p, v); }
 
 // Squared drift of the first nv lanes of a float4 pair, added in lane order.
 __device__ __forceinline__ void drift_acc(double& acc, const float x[4], const float h[4], uint32_t nv) {
