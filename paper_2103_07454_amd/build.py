@@ -17,7 +17,7 @@ SOURCES = ["evg_api.hip", "kernels_update.hip", "kernels_trigger.hip", "kernels_
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-command-line-argument"]
+         "-Wall", "-Wno-unused-command-line-argument"] + os.environ.get("EVG_EXTRA_FLAGS", "").split()
 
 
 def build_library(verbose: bool = False) -> str:

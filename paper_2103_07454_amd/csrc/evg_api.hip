@@ -289,6 +289,7 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   // ---- device tables ------------------------------------------------------
   Tables& t = c->t;
   t.P = P; t.L = L; t.C = (uint32_t)C; t.S = (uint32_t)S;
+  t.SW = ce / (uint32_t)kSweep;
   t.hist_len = cfg->thr_mode == EVG_THR_ADAPTIVE ? cfg->hist_len : 1;
   t.Ktot = (uint32_t)ktot;
   t.Npad = Npad;
@@ -322,7 +323,7 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   HIP_OR_FREE(hipMemcpyAsync(d_layers, layers.data(), L * sizeof(LayerDesc), hipMemcpyHostToDevice, c->stream));
   t.chunks = d_chunks;
   t.layers = d_layers;
-  TRY_OR_FREE(c->dalloc(&t.partials, P * C, true));
+  TRY_OR_FREE(c->dalloc(&t.partials, P * C * t.SW, true));
   TRY_OR_FREE(c->dalloc(&t.delta, S, false));
   TRY_OR_FREE(c->dalloc(&t.last_norm, S, true));
   TRY_OR_FREE(c->dalloc(&t.delta_before, S, true));
@@ -346,9 +347,14 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
     TRY_OR_FREE(c->dalloc(&t.hist, S * kHistBins, true));
     TRY_OR_FREE(c->dalloc(&t.sel_prefix, S, true));
     TRY_OR_FREE(c->dalloc(&t.sel_krem, S, true));
+    TRY_OR_FREE(c->dalloc(&t.stage_n, P * C, true));
+    TRY_OR_FREE(c->dalloc(&t.stage_key, (uint64_t)P * Npad, false));
+    TRY_OR_FREE(c->dalloc(&t.stage_idx, (uint64_t)P * Npad, false));
+    TRY_OR_FREE(c->dalloc(&t.stage_val, (uint64_t)P * Npad, false));
     TRY_OR_FREE(c->dalloc(&t.chunk_cnt, P * C, true));
     TRY_OR_FREE(c->dalloc(&t.chunk_before, P * C, true));
     TRY_OR_FREE(c->dalloc(&t.chunk_out, P * C, true));
+    TRY_OR_FREE(c->dalloc(&t.chunk_sub, P * C * (t.SW + 1), true));
     TRY_OR_FREE(c->dalloc(&t.msg_idx, (uint64_t)P * ktot, true));
     TRY_OR_FREE(c->dalloc(&t.msg_val, (uint64_t)P * ktot, true));
   } else {

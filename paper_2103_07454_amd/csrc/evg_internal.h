@@ -34,7 +34,7 @@ struct Tables {
   const ChunkDesc* chunks;
   const LayerDesc* layers;
   float* x; float* xhat; float* mbox_l; float* mbox_r; float* vel;
-  double* partials;        // [P*C] sum of squared drift per chunk
+  double* partials;        // [P*C*SW] sum of squared drift per 1024-element sweep of a chunk
   float* delta; float* last_norm; float* delta_before;
   int32_t* last_event;
   uint8_t* valid_l; uint8_t* valid_r; uint8_t* fired; uint8_t* near_tie;
@@ -45,11 +45,17 @@ struct Tables {
   uint32_t* work_full; uint32_t* work_topk;   // [P*C] compact chunk lists (r*C + c)
   uint32_t* hist;          // [S*kHistBins]
   uint32_t* sel_prefix; uint32_t* sel_krem;   // [S]
+  uint32_t* stage_n;       // [P*C] staged entries per chunk (keys in or above the threshold bin)
+  uint32_t* stage_key; uint32_t* stage_idx; float* stage_val;   // [P*Npad], a chunk's entries
+                           // start at the chunk's arena offset, in ascending index order
   uint2* chunk_cnt;        // [P*C] (keys above threshold, keys equal) per chunk
   uint2* chunk_before;     // [P*C] the same, summed over the tensor's earlier chunks
   uint2* chunk_out;        // [P*C] (first message slot, winners) per chunk
+  uint32_t* chunk_sub;     // [P*C*(SW+1)] winners before each 1024-element sweep of a chunk,
+                           // as message slots (entry 0 = the chunk's first slot)
   uint32_t* msg_idx; float* msg_val;          // [P*Ktot]
   uint32_t P, L, C, S;
+  uint32_t SW;             // 1024-element sweeps per chunk
   uint32_t hist_len;
   uint32_t Ktot;           // sum of K over tensors
   uint64_t Npad;

@@ -3,64 +3,77 @@
 // ties to the lower index.  Everything here is integer work on 31-bit keys (bit
 // patterns of non-negative floats), so results are exact and repeatable.
 //
-//   select   radix search for the K-th largest key t of every fired tensor in three
-//            passes of 11 + 11 + 9 bits: per-chunk LDS histograms, merged into the
-//            tensor's global histogram with integer atomics; one workgroup per
-//            tensor then walks the histogram from the top.
-//            Then per chunk the number of keys > t and == t, and per tensor the
-//            running totals over its chunks.
-//   send     per chunk a stable compaction of the winners (key > t, or key == t
-//            while fewer than T equal keys precede it in the tensor) into the
-//            tensor's (index, value) message in ascending index order, updating
-//            xhat at the same entries; then the put: the message is read back and
-//            scattered into the two neighbours' dense mailboxes.
+// Only two kernels read the fired tensors themselves (x and xhat):
+//   k_topk_hist   pass A: per-chunk LDS histogram of key bits 30..20, merged into the
+//                 tensor's histogram with integer atomics; k_topk_pick<0> then finds
+//                 the bin b that holds the K-th largest key.
+//   k_topk_stage  copies every element whose bin is >= b ("staged": all possible
+//                 winners, roughly K plus one bin's worth) as (key, index, value) into
+//                 the chunk's staging slot in ascending index order, and histograms
+//                 bits 19..9 of the keys inside bin b.
+// The rest works on the staged entries only, a small fraction of the tensor:
+//   k_topk_hist_low   bits 8..0 of staged keys under the 22-bit prefix -> threshold key t
+//                     and T = how many keys equal to t are still needed
+//   k_topk_count      per chunk: staged keys > t and == t
+//   k_topk_chunkscan  running totals over a tensor's chunks (one wavefront per tensor)
+//   k_topk_pack       stable compaction of the winners (key > t, or key == t while fewer
+//                     than T equal keys precede it in the tensor) into the tensor's
+//                     (index, value) message, ascending indices.
+// The message is applied to xhat and to the neighbours' mailboxes by the update pass.
 #include "evg_device.h"
 
 namespace evg {
 
-__device__ __forceinline__ float4 ld4c(const float* p) { return *reinterpret_cast<const float4*>(p); }
+struct WorkItem {
+  uint32_t w, r, c, seg;
+  ChunkDesc cd;
+  size_t base;   // arena offset of the chunk
+};
 
-// PASS 0: bits 30..20, PASS 1: bits 19..9 under the prefix found so far, PASS 2: bits 8..0.
-template <int PASS, int SWEEPS>
+__device__ __forceinline__ WorkItem work_item(const Tables& T, uint32_t i) {
+  WorkItem it;
+  it.w = T.work_topk[i];
+  it.r = it.w / T.C;
+  it.c = it.w % T.C;
+  it.cd = T.chunks[it.c];
+  it.seg = it.r * T.L + it.cd.layer;
+  it.base = (size_t)it.r * T.Npad + it.cd.off;
+  return it;
+}
+
+// Adds the non-empty bins of a workgroup's LDS histogram to the tensor's histogram.
+template <int NB>
+__device__ __forceinline__ void flush_hist(const uint32_t* h, uint32_t* gh) {
+  for (uint32_t b = threadIdx.x; b < (uint32_t)NB; b += kThreads) {
+    const uint32_t v = h[b];
+    if (v) atomicAdd(&gh[b], v);
+  }
+}
+
+template <int SWEEPS>
 __global__ __launch_bounds__(kThreads) void k_topk_hist(Tables T, StepArgs A) {
-  constexpr int NB = PASS == 2 ? 512 : kHistBins;
-  __shared__ uint32_t h[NB];
+  __shared__ uint32_t h[kHistBins];
   const uint32_t n = T.counts[1];
   for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
-    const uint32_t w = T.work_topk[i];
-    const uint32_t r = w / T.C, c = w % T.C;
-    const ChunkDesc cd = T.chunks[c];
-    const uint32_t seg = r * T.L + cd.layer;
-    const uint32_t prefix = PASS == 0 ? 0u : T.sel_prefix[seg];
-    const size_t base = (size_t)r * T.Npad + cd.off;
-    for (uint32_t b = threadIdx.x; b < (uint32_t)NB; b += kThreads) h[b] = 0;
+    const WorkItem wi = work_item(T, i);
+    for (uint32_t b = threadIdx.x; b < (uint32_t)kHistBins; b += kThreads) h[b] = 0;
     __syncthreads();
 #pragma unroll
     for (int it = 0; it < SWEEPS; ++it) {
       const uint32_t e = it * kSweep + threadIdx.x * kLaneElems;
-      if (e < cd.len) {
-        const float4 x4 = ld4c(T.x + base + e);
+      if (e < wi.cd.len) {
+        const float4 x4 = ld4s(T.x + wi.base + e);
         float4 h4 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (!A.topk_key) h4 = ld4c(T.xhat + base + e);
+        if (!A.topk_key) h4 = ld4s(T.xhat + wi.base + e);
         const float xa[4] = {x4.x, x4.y, x4.z, x4.w}, ha[4] = {h4.x, h4.y, h4.z, h4.w};
-        const uint32_t nv = cd.len - e < 4u ? cd.len - e : 4u;
+        const uint32_t nv = wi.cd.len - e < 4u ? wi.cd.len - e : 4u;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if ((uint32_t)q < nv) {
-            const uint32_t key = rank_key(xa[q], ha[q], A.topk_key);
-            if (PASS == 0) atomicAdd(&h[key >> 20], 1u);
-            else if (PASS == 1) { if ((key >> 20) == prefix) atomicAdd(&h[(key >> 9) & 2047u], 1u); }
-            else { if ((key >> 9) == prefix) atomicAdd(&h[key & 511u], 1u); }
-          }
-        }
+        for (int q = 0; q < 4; ++q)
+          if ((uint32_t)q < nv) atomicAdd(&h[rank_key(xa[q], ha[q], A.topk_key) >> 20], 1u);
       }
     }
     __syncthreads();
-    uint32_t* gh = T.hist + (size_t)seg * kHistBins;
-    for (uint32_t b = threadIdx.x; b < (uint32_t)NB; b += kThreads) {
-      const uint32_t v = h[b];
-      if (v) atomicAdd(&gh[b], v);
-    }
+    flush_hist<kHistBins>(h, T.hist + (size_t)wi.seg * kHistBins);
     __syncthreads();
   }
 }
@@ -68,6 +81,7 @@ __global__ __launch_bounds__(kThreads) void k_topk_hist(Tables T, StepArgs A) {
 // One workgroup per tensor that sends a Top-K message: find the bin that holds the
 // krem-th largest key, append it to the prefix, keep what is still to be taken
 // inside that bin, and clear the histogram for the next pass.
+// PASS 0: bits 30..20, PASS 1: bits 19..9, PASS 2: bits 8..0.
 template <int PASS>
 __global__ __launch_bounds__(kThreads) void k_topk_pick(Tables T) {
   constexpr int NB = PASS == 2 ? 512 : kHistBins;
@@ -100,39 +114,109 @@ __global__ __launch_bounds__(kThreads) void k_topk_pick(Tables T) {
   }
 }
 
-// Per chunk: how many keys exceed / equal the threshold key.
 template <int SWEEPS>
-__global__ __launch_bounds__(kThreads) void k_topk_count(Tables T, StepArgs A) {
+__global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
+  __shared__ uint32_t h[kHistBins];
   __shared__ uint32_t ws[4];
   const uint32_t n = T.counts[1];
   for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
-    const uint32_t w = T.work_topk[i];
-    const uint32_t r = w / T.C, c = w % T.C;
-    const ChunkDesc cd = T.chunks[c];
-    const uint32_t t = T.sel_prefix[r * T.L + cd.layer];
-    const size_t base = (size_t)r * T.Npad + cd.off;
-    uint32_t packed = 0;    // greater in the low half, equal in the high half (both <= 8192)
-#pragma unroll
-    for (int it = 0; it < SWEEPS; ++it) {
+    const WorkItem wi = work_item(T, i);
+    const uint32_t bin = T.sel_prefix[wi.seg];
+    for (uint32_t b = threadIdx.x; b < (uint32_t)kHistBins; b += kThreads) h[b] = 0;
+    __syncthreads();
+    uint32_t run = 0;
+    for (int it = 0; it < SWEEPS; ++it) {       // uniform trip count: the scan needs every thread
       const uint32_t e = it * kSweep + threadIdx.x * kLaneElems;
-      if (e < cd.len) {
-        const float4 x4 = ld4c(T.x + base + e);
+      float xa[4] = {0.f, 0.f, 0.f, 0.f};
+      uint32_t key[4] = {0u, 0u, 0u, 0u}, take = 0;
+      if (e < wi.cd.len) {
+        const float4 x4 = ld4s(T.x + wi.base + e);
         float4 h4 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (!A.topk_key) h4 = ld4c(T.xhat + base + e);
-        const float xa[4] = {x4.x, x4.y, x4.z, x4.w}, ha[4] = {h4.x, h4.y, h4.z, h4.w};
-        const uint32_t nv = cd.len - e < 4u ? cd.len - e : 4u;
+        if (!A.topk_key) h4 = ld4s(T.xhat + wi.base + e);
+        xa[0] = x4.x; xa[1] = x4.y; xa[2] = x4.z; xa[3] = x4.w;
+        const float ha[4] = {h4.x, h4.y, h4.z, h4.w};
+        const uint32_t nv = wi.cd.len - e < 4u ? wi.cd.len - e : 4u;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           if ((uint32_t)q < nv) {
-            const uint32_t key = rank_key(xa[q], ha[q], A.topk_key);
-            packed += (key > t ? 1u : 0u) + (key == t ? 0x10000u : 0u);
+            key[q] = rank_key(xa[q], ha[q], A.topk_key);
+            const uint32_t kb = key[q] >> 20;
+            if (kb >= bin) take |= 1u << q;
+            if (kb == bin) atomicAdd(&h[(key[q] >> 9) & 2047u], 1u);
           }
         }
       }
+      uint32_t total;
+      uint32_t pos = run + block_excl_scan<4>(__popc(take), ws, &total);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if ((take >> q) & 1u) {
+          T.stage_key[wi.base + pos] = key[q];
+          T.stage_idx[wi.base + pos] = wi.cd.j0 + e + q;
+          T.stage_val[wi.base + pos] = xa[q];
+          ++pos;
+        }
+      }
+      run += total;
     }
-    uint32_t total;
-    (void)block_excl_scan<4>(packed, ws, &total);
-    if (threadIdx.x == 0) T.chunk_cnt[w] = make_uint2(total & 0xFFFFu, total >> 16);
+    if (threadIdx.x == 0) T.stage_n[wi.w] = run;
+    __syncthreads();
+    flush_hist<kHistBins>(h, T.hist + (size_t)wi.seg * kHistBins);
+    __syncthreads();
+  }
+}
+
+// The three kernels below walk a chunk's staged entries, a few hundred at most, so
+// one wavefront per chunk does it without LDS or workgroup barriers: ballots give
+// counts and ranks.  Four independent wavefronts share a workgroup.
+
+__device__ __forceinline__ uint32_t wave_slot() { return blockIdx.x * (kThreads / 64) + wave_id(); }
+__device__ __forceinline__ uint32_t wave_slots() { return gridDim.x * (kThreads / 64); }
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
+  return __popcll(mask & ((1ull << lane_id()) - 1ull));
+}
+
+// Bits 8..0 of the staged keys that carry the 22-bit prefix found so far.  Matches are
+// rare (a 2^-22 slice of the key range), so they go straight to the tensor's histogram,
+// one atomic per distinct value per 64 entries.
+__global__ __launch_bounds__(kThreads) void k_topk_hist_low(Tables T) {
+  const uint32_t n = T.counts[1];
+  for (uint32_t i = wave_slot(); i < n; i += wave_slots()) {
+    const WorkItem wi = work_item(T, i);
+    const uint32_t prefix = T.sel_prefix[wi.seg], ns = T.stage_n[wi.w];
+    uint32_t* gh = T.hist + (size_t)wi.seg * kHistBins;
+    for (uint32_t q0 = 0; q0 < ns; q0 += 64) {
+      const uint32_t q = q0 + lane_id();
+      const uint32_t key = q < ns ? T.stage_key[wi.base + q] : 0u;
+      bool pending = q < ns && (key >> 9) == prefix;
+      uint64_t todo = __ballot(pending);
+      while (todo) {                                  // uniform: every lane sees the same mask
+        const uint32_t leader = __ffsll((unsigned long long)todo) - 1;
+        const uint32_t v = __shfl(key & 511u, leader, 64);
+        const uint64_t same = __ballot(pending && (key & 511u) == v);
+        if (lane_id() == leader) atomicAdd(&gh[v], (uint32_t)__popcll(same));
+        if ((same >> lane_id()) & 1ull) pending = false;
+        todo &= ~same;
+      }
+    }
+  }
+}
+
+// Per chunk: how many staged keys exceed / equal the threshold key.  Every key above
+// the threshold is staged (its bin is >= the threshold's), so these are the chunk's counts.
+__global__ __launch_bounds__(kThreads) void k_topk_count(Tables T) {
+  const uint32_t n = T.counts[1];
+  for (uint32_t i = wave_slot(); i < n; i += wave_slots()) {
+    const WorkItem wi = work_item(T, i);
+    const uint32_t t = T.sel_prefix[wi.seg], ns = T.stage_n[wi.w];
+    uint32_t g = 0, e = 0;
+    for (uint32_t q0 = 0; q0 < ns; q0 += 64) {
+      const uint32_t q = q0 + lane_id();
+      const uint32_t key = q < ns ? T.stage_key[wi.base + q] : 0u;
+      g += __popcll(__ballot(q < ns && key > t));
+      e += __popcll(__ballot(q < ns && key == t));
+    }
+    if (lane_id() == 0) T.chunk_cnt[wi.w] = make_uint2(g, e);
   }
 }
 
@@ -161,83 +245,46 @@ __global__ __launch_bounds__(64) void k_topk_chunkscan(Tables T) {
   }
 }
 
-// Stable compaction of a chunk's winners into the tensor's message; xhat takes the
-// sent values (only those entries were communicated).
-template <int SWEEPS>
-__global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T, StepArgs A) {
-  __shared__ uint32_t ws[4];
+// Stable compaction of a chunk's winners from its staged entries into the tensor's
+// message.  Also records where each 1024-element sweep of the chunk starts in the
+// message, so that the update pass can fetch exactly its part.
+__global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
   const uint32_t n = T.counts[1];
-  for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
-    const uint32_t w = T.work_topk[i];
-    const uint32_t r = w / T.C, c = w % T.C;
-    const ChunkDesc cd = T.chunks[c];
-    const uint32_t seg = r * T.L + cd.layer;
-    const uint32_t t = T.sel_prefix[seg], ties = T.sel_krem[seg];
-    const uint2 before = T.chunk_before[w];
-    const size_t base = (size_t)r * T.Npad + cd.off;
-    const size_t mbase = (size_t)r * T.Ktot + T.layers[cd.layer].msg_off;
+  for (uint32_t i = wave_slot(); i < n; i += wave_slots()) {
+    const WorkItem wi = work_item(T, i);
+    const uint32_t t = T.sel_prefix[wi.seg], ties = T.sel_krem[wi.seg], ns = T.stage_n[wi.w];
+    const uint2 before = T.chunk_before[wi.w];
+    const size_t mbase = (size_t)wi.r * T.Ktot + T.layers[wi.cd.layer].msg_off;
+    uint32_t* sub = T.chunk_sub + (size_t)wi.w * (T.SW + 1);
+    const uint32_t first = before.x + (before.y < ties ? before.y : ties);   // the chunk's first slot
     uint32_t run_g = before.x, run_e = before.y;
-    for (int it = 0; it < SWEEPS; ++it) {          // uniform trip count: scans need every thread
-      const uint32_t e = it * kSweep + threadIdx.x * kLaneElems;
-      float xa[4] = {0.f, 0.f, 0.f, 0.f}, ha[4] = {0.f, 0.f, 0.f, 0.f};
-      uint32_t isg = 0, ise = 0, nv = 0;
-      if (e < cd.len) {
-        const float4 x4 = ld4c(T.x + base + e), h4 = ld4c(T.xhat + base + e);
-        xa[0] = x4.x; xa[1] = x4.y; xa[2] = x4.z; xa[3] = x4.w;
-        ha[0] = h4.x; ha[1] = h4.y; ha[2] = h4.z; ha[3] = h4.w;
-        nv = cd.len - e < 4u ? cd.len - e : 4u;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if ((uint32_t)q < nv) {
-            const uint32_t key = rank_key(xa[q], ha[q], A.topk_key);
-            isg |= (key > t ? 1u : 0u) << q;
-            ise |= (key == t ? 1u : 0u) << q;
-          }
-        }
+    uint32_t per_sweep[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // winners per sweep (wave-uniform)
+    for (uint32_t q0 = 0; q0 < ns; q0 += 64) {
+      const uint32_t q = q0 + lane_id();
+      uint32_t key = 0, j = wi.cd.j0;
+      if (q < ns) { key = T.stage_key[wi.base + q]; j = T.stage_idx[wi.base + q]; }
+      const bool isg = q < ns && key > t, ise = q < ns && key == t;
+      const uint64_t mg = __ballot(isg), me = __ballot(ise);
+      const uint32_t g = run_g + lanes_below(mg), eq = run_e + lanes_below(me);
+      const bool win = isg || (ise && eq < ties);
+      if (win) {
+        const uint32_t pos = g + (eq < ties ? eq : ties);
+        T.msg_idx[mbase + pos] = j;
+        T.msg_val[mbase + pos] = T.stage_val[wi.base + q];
       }
-      const uint32_t mine = __popc(isg) + (__popc(ise) << 16);
-      uint32_t total;
-      const uint32_t ex = block_excl_scan<4>(mine, ws, &total);
-      uint32_t g = run_g + (ex & 0xFFFFu), q_e = run_e + (ex >> 16);
-      bool any = false;
+      const uint32_t sw = (j - wi.cd.j0) / (uint32_t)kSweep;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const bool bg = (isg >> q) & 1u, be = (ise >> q) & 1u;
-        const bool win = bg || (be && q_e < ties);
-        if (win) {
-          const uint32_t pos = g + (q_e < ties ? q_e : ties);
-          T.msg_idx[mbase + pos] = cd.j0 + e + q;
-          T.msg_val[mbase + pos] = xa[q];
-          ha[q] = xa[q];
-          any = true;
-        }
-        g += bg ? 1u : 0u;
-        q_e += be ? 1u : 0u;
-      }
-      if (any) *reinterpret_cast<float4*>(T.xhat + base + e) = make_float4(ha[0], ha[1], ha[2], ha[3]);
-      run_g += total & 0xFFFFu;
-      run_e += total >> 16;
+      for (uint32_t s2 = 0; s2 < 8; ++s2)
+        if (s2 < T.SW) per_sweep[s2] += __popcll(__ballot(win && sw == s2));
+      run_g += __popcll(mg);
+      run_e += __popcll(me);
     }
-  }
-}
-
-// The put: each chunk's slice of the message is scattered into the receivers' dense copies.
-__global__ __launch_bounds__(kThreads) void k_topk_put(Tables T) {
-  const uint32_t n = T.counts[1];
-  for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
-    const uint32_t w = T.work_topk[i];
-    const uint32_t r = w / T.C, c = w % T.C;
-    const LayerDesc ld = T.layers[T.chunks[c].layer];
-    const uint2 out = T.chunk_out[w];
-    const uint32_t left = (r + T.P - 1) % T.P, right = (r + 1) % T.P;
-    const size_t mbase = (size_t)r * T.Ktot + ld.msg_off + out.x;
-    float* toR = T.mbox_r + (size_t)left * T.Npad + ld.off;
-    float* toL = T.mbox_l + (size_t)right * T.Npad + ld.off;
-    for (uint32_t q = threadIdx.x; q < out.y; q += kThreads) {
-      const uint32_t j = T.msg_idx[mbase + q];
-      const float v = T.msg_val[mbase + q];
-      toR[j] = v;
-      toL[j] = v;
+    if (lane_id() == 0) {
+      uint32_t at = first;
+#pragma unroll
+      for (uint32_t s2 = 0; s2 < 8; ++s2)
+        if (s2 < T.SW) { sub[s2] = at; at += per_sweep[s2]; }
+      sub[T.SW] = at;
     }
   }
 }
@@ -245,14 +292,12 @@ __global__ __launch_bounds__(kThreads) void k_topk_put(Tables T) {
 template <int SWEEPS>
 static void select_s(const Tables& t, const StepArgs& a, uint32_t grid, hipStream_t s) {
   const dim3 g(grid), b(kThreads), segs(t.S);
-  k_topk_hist<0, SWEEPS><<<g, b, 0, s>>>(t, a);
+  k_topk_hist<SWEEPS><<<g, b, 0, s>>>(t, a);
   k_topk_pick<0><<<segs, b, 0, s>>>(t);
-  k_topk_hist<1, SWEEPS><<<g, b, 0, s>>>(t, a);
+  k_topk_stage<SWEEPS><<<g, b, 0, s>>>(t, a);
   k_topk_pick<1><<<segs, b, 0, s>>>(t);
-  k_topk_hist<2, SWEEPS><<<g, b, 0, s>>>(t, a);
+  k_topk_hist_low<<<g, b, 0, s>>>(t);
   k_topk_pick<2><<<segs, b, 0, s>>>(t);
-  k_topk_count<SWEEPS><<<g, b, 0, s>>>(t, a);
-  k_topk_chunkscan<<<segs, dim3(64), 0, s>>>(t);
 }
 
 hipError_t launch_topk_select(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid,
@@ -267,17 +312,11 @@ hipError_t launch_topk_select(const Tables& t, const StepArgs& a, uint32_t chunk
   return hipGetLastError();
 }
 
-hipError_t launch_topk_send(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid,
-                            hipStream_t s) {
+hipError_t launch_topk_send(const Tables& t, const StepArgs&, uint32_t, uint32_t grid, hipStream_t s) {
   const dim3 g(grid), b(kThreads);
-  switch (chunk_elems / kSweep) {
-    case 1: k_topk_pack<1><<<g, b, 0, s>>>(t, a); break;
-    case 2: k_topk_pack<2><<<g, b, 0, s>>>(t, a); break;
-    case 4: k_topk_pack<4><<<g, b, 0, s>>>(t, a); break;
-    case 8: k_topk_pack<8><<<g, b, 0, s>>>(t, a); break;
-    default: return hipErrorInvalidValue;
-  }
-  k_topk_put<<<g, b, 0, s>>>(t);
+  k_topk_count<<<g, b, 0, s>>>(t);
+  k_topk_chunkscan<<<dim3(t.S), dim3(64), 0, s>>>(t);
+  k_topk_pack<<<g, b, 0, s>>>(t);
   return hipGetLastError();
 }
 

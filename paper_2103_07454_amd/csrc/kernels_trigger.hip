@@ -17,9 +17,10 @@ __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
   if (seg >= T.S) return;           // whole wavefront leaves; no workgroup barrier below
   const uint32_t r = seg / T.L, l = seg % T.L;
   const LayerDesc ld = T.layers[l];
-  const double* part = T.partials + (size_t)r * T.C + ld.chunk0;
+  const double* part = T.partials + ((size_t)r * T.C + ld.chunk0) * T.SW;
+  const uint32_t np = ld.nchunks * T.SW;
   double acc = 0.0;
-  for (uint32_t i = lane_id(); i < ld.nchunks; i += 64) acc += part[i];
+  for (uint32_t i = lane_id(); i < np; i += 64) acc += part[i];
   acc = wave_sum(acc);
   if (lane_id() != 0) return;
 

@@ -3,8 +3,16 @@
 // of Section 4), which also accumulates the squared drift || x - xhat ||^2 that the
 // next iteration's trigger test needs, and a stand-alone drift-norm pass.
 //
-// One workgroup (256 threads) owns one chunk of one tensor of one worker and sweeps
-// it in float4 steps; HBM-bound: 5 reads + 2 writes of 4 bytes per element.
+// One workgroup (256 threads, one float4 per thread) owns one 1024-element sweep of
+// one chunk of one worker: the launch shape that streams best on MI355X.  HBM-bound:
+// 5 reads + 2 writes of 4 bytes per element.
+//
+// Top-K messages are applied here, where the dense arrays pass through registers
+// anyway: the sender's own message patches xhat (only the sent entries count as
+// communicated), the left and right neighbours' messages patch the two mailboxes
+// (the receiving end of the put, Section 6).  A message slice is scattered into an
+// LDS window first, so that global accesses stay 16-byte wide and coalesced, and a
+// float4 is written back only if it changed.
 #include "evg_device.h"
 
 namespace evg {
@@ -23,81 +31,151 @@ __device__ __forceinline__ void drift_acc(double& acc, const float x[4], const f
   }
 }
 
-template <int SWEEPS>
 __global__ __launch_bounds__(kThreads) void k_norm(Tables T) {
   __shared__ double ws[4];
-  const uint32_t c = blockIdx.x, r = blockIdx.y;
+  const uint32_t c = blockIdx.x / T.SW, sub = blockIdx.x % T.SW, r = blockIdx.y;
   const ChunkDesc cd = T.chunks[c];
   const size_t base = (size_t)r * T.Npad + cd.off;
+  const uint32_t e = sub * kSweep + threadIdx.x * kLaneElems;
   double acc = 0.0;
-#pragma unroll
-  for (int it = 0; it < SWEEPS; ++it) {
-    const uint32_t e = it * kSweep + threadIdx.x * kLaneElems;
-    if (e < cd.len) {
-      const float4 x4 = ld4(T.x + base + e), h4 = ld4(T.xhat + base + e);
-      const float xa[4] = {x4.x, x4.y, x4.z, x4.w}, ha[4] = {h4.x, h4.y, h4.z, h4.w};
-      const uint32_t nv = cd.len - e < 4u ? cd.len - e : 4u;
-      drift_acc(acc, xa, ha, nv);
-    }
+  if (e < cd.len) {
+    const float4 x4 = ld4(T.x + base + e), h4 = ld4(T.xhat + base + e);
+    const float xa[4] = {x4.x, x4.y, x4.z, x4.w}, ha[4] = {h4.x, h4.y, h4.z, h4.w};
+    const uint32_t nv = cd.len - e < 4u ? cd.len - e : 4u;
+    drift_acc(acc, xa, ha, nv);
   }
   const double total = block_sum(acc, ws);
-  if (threadIdx.x == 0) T.partials[(size_t)r * T.C + c] = total;
+  if (threadIdx.x == 0) T.partials[((size_t)r * T.C + c) * T.SW + sub] = total;
+}
+
+// One source of a sparse patch for this workgroup's 1024-element window: the slice
+// of worker `src`'s message that chunk c, sweep sub produced (empty if `src` sent no
+// Top-K message for this tensor in this iteration).
+struct Slice { size_t at; uint32_t n; };
+
+__device__ __forceinline__ Slice message_slice(const Tables& T, uint32_t src, uint32_t layer, uint32_t c,
+                                               uint32_t sub, uint32_t msg_off) {
+  Slice s;
+  const size_t w = (size_t)src * T.C + c;
+  const uint32_t lo = T.chunk_sub[w * (T.SW + 1) + sub], hi = T.chunk_sub[w * (T.SW + 1) + sub + 1];
+  s.at = (size_t)src * T.Ktot + msg_off + lo;
+  s.n = T.fired[src * T.L + layer] == 2 ? hi - lo : 0u;
+  return s;
+}
+
+// Scatters a slice into its LDS window (values + one bit per element).
+__device__ __forceinline__ void scatter_slice(const Tables& T, const Slice& s, uint32_t j_lo, float* pv,
+                                              uint32_t* pm) {
+  for (uint32_t q = threadIdx.x; q < s.n; q += kThreads) {
+    const uint32_t loc = T.msg_idx[s.at + q] - j_lo;
+    if (loc < (uint32_t)kSweep) {
+      pv[loc] = T.msg_val[s.at + q];
+      atomicOr(&pm[loc >> 5], 1u << (loc & 31u));
+    }
+  }
+}
+
+#ifndef EVG_WB_LANES
+#define EVG_WB_LANES 4
+#endif
+// OR of a per-lane flag over the aligned group of EVG_WB_LANES neighbouring lanes.
+__device__ __forceinline__ uint32_t group_any(uint32_t v) {
+#pragma unroll
+  for (int o = 1; o < EVG_WB_LANES; o <<= 1) v |= __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Replaces this thread's lanes by the window's entries; returns the mask of replaced lanes.
+__device__ __forceinline__ uint32_t take_patch(const float* pv, const uint32_t* pm, float a[4]) {
+  const uint32_t l0 = threadIdx.x * kLaneElems;
+  const uint32_t bits = (pm[l0 >> 5] >> (l0 & 31u)) & 0xFu;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if ((bits >> i) & 1u) a[i] = pv[l0 + i];
+  return bits;
 }
 
 // DIST: 0 normal (one Philox block per float4), 1 Student-t(3) (one block per element).
-// GRADBUF: gradients come from a caller buffer.  NORM: also write the chunk's squared drift.
-template <int SWEEPS, int DIST, bool GRADBUF, bool NORM>
+// GRADBUF: gradients come from a caller buffer.  NORM: also write the sweep's squared drift.
+// TOPK: messages of this iteration may have to be applied.
+template <int DIST, bool GRADBUF, bool NORM, bool TOPK>
 __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   __shared__ double ws[4];
-  const uint32_t c = blockIdx.x, r = blockIdx.y;
+  __shared__ float pv[TOPK ? 3 * kSweep : 1];   // LDS windows of the three patches
+  __shared__ uint32_t pm[96];
+  const uint32_t c = blockIdx.x / T.SW, sub = blockIdx.x % T.SW, r = blockIdx.y;
   const ChunkDesc cd = T.chunks[c];
   const uint32_t seg = r * T.L + cd.layer;
   const bool vl = T.valid_l[seg] != 0, vr = T.valid_r[seg] != 0;
   const size_t base = (size_t)r * T.Npad + cd.off;
   const float third = 0.333333343f;   // (float)(1/3): the ring's mixing weight
-  float sg = 0.0f;
-  bool spike = false;
-  if (!GRADBUF) {
-    sg = (float)(T.layers[cd.layer].sig_base * A.decay_pow);
-    if (A.spike_prob > 0.0f) {
-      const Rand4 sp = philox(0u, 0xFFFFFFFFu, A.k, r, A.key0, A.key1);
-      spike = unit_open(sp.w[0]) < A.spike_prob;
-    }
-  }
+  const uint32_t e = sub * kSweep + threadIdx.x * kLaneElems;
+  const bool live = e < cd.len;
   double acc = 0.0;
-#pragma unroll
-  for (int it = 0; it < SWEEPS; ++it) {
-    const uint32_t e = it * kSweep + threadIdx.x * kLaneElems;
-    if (e < cd.len) {
+  if (sub * kSweep < cd.len) {        // uniform: this sweep holds elements
+    float xa[4] = {0.f, 0.f, 0.f, 0.f}, va[4] = {0.f, 0.f, 0.f, 0.f};
+    float la[4] = {0.f, 0.f, 0.f, 0.f}, ra[4] = {0.f, 0.f, 0.f, 0.f}, ha[4] = {0.f, 0.f, 0.f, 0.f};
+    float g[4] = {0.f, 0.f, 0.f, 0.f};
+    if (live) {
       const float4 x4 = ld4(T.x + base + e), v4 = ld4(T.vel + base + e);
-      float4 l4 = make_float4(0.f, 0.f, 0.f, 0.f), r4 = l4, h4 = l4;
-      if (vl) l4 = ld4(T.mbox_l + base + e);
-      if (vr) r4 = ld4(T.mbox_r + base + e);
-      if (NORM) h4 = ld4(T.xhat + base + e);
-      float g[4];
-      if (GRADBUF) {
-        const float4 g4 = ld4(A.grad + base + e);
-        g[0] = g4.x; g[1] = g4.y; g[2] = g4.z; g[3] = g4.w;
-      } else if (DIST == 0) {
-        float z[4];
-        normals4(philox((cd.j0 + e) >> 2, cd.layer, A.k, r, A.key0, A.key1), z);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) g[i] = sg * z[i];
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
+      xa[0] = x4.x; xa[1] = x4.y; xa[2] = x4.z; xa[3] = x4.w;
+      va[0] = v4.x; va[1] = v4.y; va[2] = v4.z; va[3] = v4.w;
+      if (vl) { const float4 t = ld4(T.mbox_l + base + e); la[0] = t.x; la[1] = t.y; la[2] = t.z; la[3] = t.w; }
+      if (vr) { const float4 t = ld4(T.mbox_r + base + e); ra[0] = t.x; ra[1] = t.y; ra[2] = t.z; ra[3] = t.w; }
+      if (NORM || TOPK) { const float4 t = ld4(T.xhat + base + e); ha[0] = t.x; ha[1] = t.y; ha[2] = t.z; ha[3] = t.w; }
+      if (GRADBUF) { const float4 t = ld4(A.grad + base + e); g[0] = t.x; g[1] = t.y; g[2] = t.z; g[3] = t.w; }
+    }
+    if (TOPK) {
+      // three sparse patches of this iteration: my own message (what xhat must now
+      // hold) and the two messages that arrive in my mailboxes
+      const uint32_t left = (r + T.P - 1) % T.P, right = (r + 1) % T.P;
+      const uint32_t moff = T.layers[cd.layer].msg_off, j_lo = cd.j0 + sub * kSweep;
+      const Slice s0 = message_slice(T, r, cd.layer, c, sub, moff);
+      const Slice s1 = message_slice(T, left, cd.layer, c, sub, moff);
+      const Slice s2 = message_slice(T, right, cd.layer, c, sub, moff);
+      if (s0.n | s1.n | s2.n) {          // uniform
+        if (threadIdx.x < 96) pm[threadIdx.x] = 0;
+        __syncthreads();
+        scatter_slice(T, s0, j_lo, pv, pm);
+        scatter_slice(T, s1, j_lo, pv + kSweep, pm + 32);
+        scatter_slice(T, s2, j_lo, pv + 2 * kSweep, pm + 64);
+        __syncthreads();
+        const uint32_t b0 = take_patch(pv, pm, ha);
+        const uint32_t b1 = take_patch(pv + kSweep, pm + 32, la);
+        const uint32_t b2 = take_patch(pv + 2 * kSweep, pm + 64, ra);
+        // Write back whole aligned groups of EVG_WB_LANES float4s (64 or 128 bytes) in
+        // which anything changed: scattered 16-byte writes cost far more in HBM than
+        // the few unchanged bytes a full line carries.
+        const uint32_t w0 = group_any(b0), w1 = group_any(b1), w2 = group_any(b2);
+        if (live && w0) st4(T.xhat + base + e, make_float4(ha[0], ha[1], ha[2], ha[3]));
+        if (live && w1) st4(T.mbox_l + base + e, make_float4(la[0], la[1], la[2], la[3]));
+        if (live && w2) st4(T.mbox_r + base + e, make_float4(ra[0], ra[1], ra[2], ra[3]));
+      }
+    }
+    if (live) {
+      if (!GRADBUF) {
+        const float sg = (float)(T.layers[cd.layer].sig_base * A.decay_pow);
+        if (DIST == 0) {
           float z[4];
-          normals4(philox(cd.j0 + e + i, cd.layer, A.k, r, A.key0, A.key1), z);
-          g[i] = sg * student_t3(z);
+          normals4(philox((cd.j0 + e) >> 2, cd.layer, A.k, r, A.key0, A.key1), z);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) g[i] = sg * z[i];
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float z[4];
+            normals4(philox(cd.j0 + e + i, cd.layer, A.k, r, A.key0, A.key1), z);
+            g[i] = sg * student_t3(z);
+          }
+        }
+        if (A.spike_prob > 0.0f) {
+          const Rand4 sp = philox(0u, 0xFFFFFFFFu, A.k, r, A.key0, A.key1);
+          if (unit_open(sp.w[0]) < A.spike_prob) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) g[i] = g[i] * A.spike_gain;
+          }
         }
       }
-      if (!GRADBUF && spike) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) g[i] = g[i] * A.spike_gain;
-      }
-      float xa[4] = {x4.x, x4.y, x4.z, x4.w}, va[4] = {v4.x, v4.y, v4.z, v4.w};
-      const float la[4] = {l4.x, l4.y, l4.z, l4.w}, ra[4] = {r4.x, r4.y, r4.z, r4.w};
-      const float ha[4] = {h4.x, h4.y, h4.z, h4.w};
       const uint32_t nv = cd.len - e < 4u ? cd.len - e : 4u;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -116,7 +194,7 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   }
   if (NORM) {
     const double total = block_sum(acc, ws);
-    if (threadIdx.x == 0) T.partials[(size_t)r * T.C + c] = total;
+    if (threadIdx.x == 0) T.partials[((size_t)r * T.C + c) * T.SW + sub] = total;
   }
 }
 
@@ -133,42 +211,28 @@ __global__ __launch_bounds__(kThreads) void k_average(Tables T, float* out) {
   st4(out + q * 4, make_float4((float)(a0 / p), (float)(a1 / p), (float)(a2 / p), (float)(a3 / p)));
 }
 
-hipError_t launch_norm(const Tables& t, uint32_t chunk_elems, hipStream_t s) {
-  const dim3 grid(t.C, t.P), block(kThreads);
-  switch (chunk_elems / kSweep) {
-    case 1: k_norm<1><<<grid, block, 0, s>>>(t); break;
-    case 2: k_norm<2><<<grid, block, 0, s>>>(t); break;
-    case 4: k_norm<4><<<grid, block, 0, s>>>(t); break;
-    case 8: k_norm<8><<<grid, block, 0, s>>>(t); break;
-    default: return hipErrorInvalidValue;
-  }
+hipError_t launch_norm(const Tables& t, uint32_t, hipStream_t s) {
+  k_norm<<<dim3(t.C * t.SW, t.P), dim3(kThreads), 0, s>>>(t);
   return hipGetLastError();
 }
 
-template <int SWEEPS>
-static void launch_update_s(const Tables& t, const StepArgs& a, uint32_t dist, uint32_t grad_mode,
-                            bool norm, hipStream_t s) {
-  const dim3 grid(t.C, t.P), block(kThreads);
-  if (grad_mode == 1) {
-    if (norm) k_update<SWEEPS, 0, true, true><<<grid, block, 0, s>>>(t, a);
-    else k_update<SWEEPS, 0, true, false><<<grid, block, 0, s>>>(t, a);
-  } else if (dist == 0) {
-    if (norm) k_update<SWEEPS, 0, false, true><<<grid, block, 0, s>>>(t, a);
-    else k_update<SWEEPS, 0, false, false><<<grid, block, 0, s>>>(t, a);
-  } else {
-    if (norm) k_update<SWEEPS, 1, false, true><<<grid, block, 0, s>>>(t, a);
-    else k_update<SWEEPS, 1, false, false><<<grid, block, 0, s>>>(t, a);
-  }
+template <bool NORM, bool TOPK>
+static void launch_update_v(const Tables& t, const StepArgs& a, uint32_t dist, uint32_t grad_mode,
+                            hipStream_t s) {
+  const dim3 grid(t.C * t.SW, t.P), block(kThreads);
+  if (grad_mode == 1) k_update<0, true, NORM, TOPK><<<grid, block, 0, s>>>(t, a);
+  else if (dist == 0) k_update<0, false, NORM, TOPK><<<grid, block, 0, s>>>(t, a);
+  else k_update<1, false, NORM, TOPK><<<grid, block, 0, s>>>(t, a);
 }
 
-hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t dist,
+hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t, uint32_t dist,
                          uint32_t grad_mode, bool fused_norm, hipStream_t s) {
-  switch (chunk_elems / kSweep) {
-    case 1: launch_update_s<1>(t, a, dist, grad_mode, fused_norm, s); break;
-    case 2: launch_update_s<2>(t, a, dist, grad_mode, fused_norm, s); break;
-    case 4: launch_update_s<4>(t, a, dist, grad_mode, fused_norm, s); break;
-    case 8: launch_update_s<8>(t, a, dist, grad_mode, fused_norm, s); break;
-    default: return hipErrorInvalidValue;
+  if (a.topk_on) {
+    if (fused_norm) launch_update_v<true, true>(t, a, dist, grad_mode, s);
+    else launch_update_v<false, true>(t, a, dist, grad_mode, s);
+  } else {
+    if (fused_norm) launch_update_v<true, false>(t, a, dist, grad_mode, s);
+    else launch_update_v<false, false>(t, a, dist, grad_mode, s);
   }
   return hipGetLastError();
 }
