@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-timers", action="store_true")
+    ap.add_argument("--diag-grad-buffer", action="store_true",
+                    help="diagnostic only (not the named workload): gradients from a fixed device buffer")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the parameter path of all P simulated workers on ONE GPU; "
@@ -71,12 +73,18 @@ def main():
     x0 = w.x0()[None, :]                       # common start; uploaded once per worker slice
     x0 = np.broadcast_to(x0, (w.P, w.N))
 
+    gbuf = None
+
     def make():
+        if args.diag_grad_buffer:
+            return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk, grad_mode=evg.GRAD_BUFFER)
         return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk)
 
     ring = make()
+    if args.diag_grad_buffer:
+        gbuf = torch.randn_like(ring.x) * 1e-4
     for k in range(args.warmup):
-        ring.step(k)
+        ring.step(k, gbuf)
     ring.synchronize()
     ring.close()
     del ring
@@ -88,7 +96,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        ring.step(k)
+        ring.step(k, gbuf)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -108,9 +116,9 @@ def main():
         "ms_per_step": 1e3 * dt / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
+        "config": {"workload": w.name + ("+DIAG_GRAD_BUFFER" if args.diag_grad_buffer else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
                    "threshold": "adaptive" if w.thr_mode else "fixed", "topk_ppm": w.topk_ppm,
-                   "chunk_elems": args.chunk or 4096,
+                   "chunk_elems": args.chunk or 8192,
                    "fraction_fired_full": f_full, "fraction_fired_topk": f_topk,
                    "messages_pct_of_regular": 100.0 * st["events_total"] / max(1, st["regular_events"]),
                    "communication_pct_of_regular":

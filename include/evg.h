@@ -83,9 +83,11 @@ typedef struct {
   uint32_t topk_key;            /* EVG_KEY_*: rank by |x - xhat| or by |x|              */
   uint32_t grad_mode;           /* EVG_GRAD_*                                           */
   uint32_t norm_mode;           /* EVG_NORM_FUSED: the update pass also accumulates the
-                                   next iteration's drift norms; EVG_NORM_SEPARATE: a
-                                   pass of its own reads x and xhat                     */
-  uint32_t chunk_elems;         /* work granule: 0 (= 4096), 1024, 2048, 4096 or 8192   */
+                                   next iteration's drift norms (and the first radix
+                                   histogram of its Top-K selection); EVG_NORM_SEPARATE:
+                                   passes of their own read x and xhat                  */
+  uint32_t chunk_elems;         /* work granule of the send kernels: 0 (= 8192), 1024,
+                                   2048, 4096 or 8192 elements; no tensor shares one    */
   evg_synth synth;
   /* DEVICE arenas owned by the caller, each P * evg_padded_numel() floats,
    * 16-byte aligned, non-overlapping, alive until evg_destroy.  Worker r's

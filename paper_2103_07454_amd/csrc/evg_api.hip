@@ -47,7 +47,7 @@ struct evg_ctx {
   evg_config cfg{};
   hipStream_t stream = nullptr;
   Tables t{};
-  uint32_t chunk_elems = 4096;
+  uint32_t chunk_elems = 8192;
   uint32_t work_grid = 1;
   std::vector<uint64_t> numel;      // per tensor
   std::vector<uint32_t> K;          // per tensor Top-K message length
@@ -203,7 +203,7 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   if (cfg->topk_key > EVG_KEY_ABS_VALUE) return fail(EVG_ERR_INVALID, "unknown topk_key %u", cfg->topk_key);
   if (cfg->grad_mode > EVG_GRAD_BUFFER) return fail(EVG_ERR_INVALID, "unknown grad_mode %u", cfg->grad_mode);
   if (cfg->norm_mode > EVG_NORM_SEPARATE) return fail(EVG_ERR_INVALID, "unknown norm_mode %u", cfg->norm_mode);
-  const uint32_t ce = cfg->chunk_elems ? cfg->chunk_elems : 4096u;
+  const uint32_t ce = cfg->chunk_elems ? cfg->chunk_elems : 8192u;
   if (ce != 1024 && ce != 2048 && ce != 4096 && ce != 8192)
     return fail(EVG_ERR_INVALID, "chunk_elems must be 0, 1024, 2048, 4096 or 8192");
   if (cfg->grad_mode == EVG_GRAD_SYNTH) {
@@ -280,9 +280,9 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
     off += pad_to(n, 4);
   }
   const uint64_t C = chunks.size();
-  if ((uint64_t)P * C > 0xFFFFFFF0ull || ktot > 0xFFFFFFF0ull) {
+  if ((uint64_t)P * C * (ce / 1024 + 1) > 0xFFFFFFF0ull || (uint64_t)P * ktot > 0xFFFFFFF0ull) {
     delete c;
-    return fail(EVG_ERR_INVALID, "too many chunks for 32-bit work lists");
+    return fail(EVG_ERR_INVALID, "configuration too large: work lists and message slots are indexed with 32 bits");
   }
   const uint64_t S = (uint64_t)P * L;
 
@@ -394,6 +394,7 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   a.force_first = g.force_first ? 1u : 0u;
   a.topk_on = g.topk_ppm ? 1u : 0u;
   a.topk_key = g.topk_key;
+  a.hist_fused = (g.topk_ppm && g.norm_mode == EVG_NORM_FUSED) ? 1u : 0u;
   a.key0 = (uint32_t)g.synth.seed;
   a.key1 = (uint32_t)(g.synth.seed >> 32);
   a.decay_pow = std::pow(g.synth.decay, (double)iter);

@@ -69,6 +69,7 @@ struct StepArgs {
   uint32_t force_first;
   uint32_t topk_on;
   uint32_t topk_key;
+  uint32_t hist_fused;     // the update pass of the previous iteration already built pass A's histograms
   uint32_t key0, key1;
   double decay_pow;        // decay^k
   float spike_prob, spike_gain;

@@ -88,9 +88,15 @@ __global__ __launch_bounds__(kThreads) void k_topk_pick(Tables T) {
   constexpr int PER = NB / kThreads;
   __shared__ uint32_t ws[4];
   const uint32_t seg = blockIdx.x;
-  if (T.fired[seg] != 2) return;    // uniform for the workgroup
-  const uint32_t krem = PASS == 0 ? T.layers[seg % T.L].K : T.sel_krem[seg];
   uint32_t* gh = T.hist + (size_t)seg * kHistBins;
+  if (T.fired[seg] != 2) {          // uniform for the workgroup
+    // pass A histograms are built for every tensor when the update pass makes them:
+    // those of tensors that stay silent are simply dropped
+    if (PASS == 0)
+      for (uint32_t b = threadIdx.x; b < (uint32_t)kHistBins; b += kThreads) gh[b] = 0;
+    return;
+  }
+  const uint32_t krem = PASS == 0 ? T.layers[seg % T.L].K : T.sel_krem[seg];
   const uint32_t top = NB - 1 - threadIdx.x * PER;   // this thread's highest bin
   uint32_t cnt[PER], local = 0;
 #pragma unroll
@@ -292,7 +298,7 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
 template <int SWEEPS>
 static void select_s(const Tables& t, const StepArgs& a, uint32_t grid, hipStream_t s) {
   const dim3 g(grid), b(kThreads), segs(t.S);
-  k_topk_hist<SWEEPS><<<g, b, 0, s>>>(t, a);
+  if (!a.hist_fused) k_topk_hist<SWEEPS><<<g, b, 0, s>>>(t, a);
   k_topk_pick<0><<<segs, b, 0, s>>>(t);
   k_topk_stage<SWEEPS><<<g, b, 0, s>>>(t, a);
   k_topk_pick<1><<<segs, b, 0, s>>>(t);

@@ -51,14 +51,14 @@ __global__ __launch_bounds__(kThreads) void k_norm(Tables T) {
 // One source of a sparse patch for this workgroup's 1024-element window: the slice
 // of worker `src`'s message that chunk c, sweep sub produced (empty if `src` sent no
 // Top-K message for this tensor in this iteration).
-struct Slice { size_t at; uint32_t n; };
+struct Slice { uint32_t at; uint32_t n; };   // P*Ktot and P*C*(SW+1) fit 32 bits (checked at init)
 
 __device__ __forceinline__ Slice message_slice(const Tables& T, uint32_t src, uint32_t layer, uint32_t c,
                                                uint32_t sub, uint32_t msg_off) {
   Slice s;
-  const size_t w = (size_t)src * T.C + c;
-  const uint32_t lo = T.chunk_sub[w * (T.SW + 1) + sub], hi = T.chunk_sub[w * (T.SW + 1) + sub + 1];
-  s.at = (size_t)src * T.Ktot + msg_off + lo;
+  const uint32_t w = (src * T.C + c) * (T.SW + 1) + sub;
+  const uint32_t lo = T.chunk_sub[w], hi = T.chunk_sub[w + 1];
+  s.at = src * T.Ktot + msg_off + lo;
   s.n = T.fired[src * T.L + layer] == 2 ? hi - lo : 0u;
   return s;
 }
@@ -75,34 +75,37 @@ __device__ __forceinline__ void scatter_slice(const Tables& T, const Slice& s, u
   }
 }
 
-#ifndef EVG_WB_LANES
-#define EVG_WB_LANES 4
-#endif
-// OR of a per-lane flag over the aligned group of EVG_WB_LANES neighbouring lanes.
-__device__ __forceinline__ uint32_t group_any(uint32_t v) {
-#pragma unroll
-  for (int o = 1; o < EVG_WB_LANES; o <<= 1) v |= __shfl_xor(v, o, 64);
-  return v;
-}
-
-// Replaces this thread's lanes by the window's entries; returns the mask of replaced lanes.
+// Replaces this thread's lanes by the window's entries.  Returns the change mask of
+// the aligned 64-byte group (4 neighbouring float4s) this thread's float4 belongs to:
+// write-back is decided per group, because scattered 16-byte writes cost far more in
+// HBM than the few unchanged bytes a full 64-byte line carries.
 __device__ __forceinline__ uint32_t take_patch(const float* pv, const uint32_t* pm, float a[4]) {
-  const uint32_t l0 = threadIdx.x * kLaneElems;
-  const uint32_t bits = (pm[l0 >> 5] >> (l0 & 31u)) & 0xFu;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    if ((bits >> i) & 1u) a[i] = pv[l0 + i];
-  return bits;
+  const uint32_t l0 = threadIdx.x * kLaneElems;          // first element of this thread
+  const uint32_t g0 = l0 & ~15u;                         // first element of its 64-byte group
+  const uint32_t group = (pm[g0 >> 5] >> (g0 & 31u)) & 0xFFFFu;
+  const uint32_t bits = (group >> (l0 & 15u)) & 0xFu;
+  const float4 v = *reinterpret_cast<const float4*>(pv + l0);   // unwritten lanes hold garbage: masked
+  a[0] = (bits & 1u) ? v.x : a[0];
+  a[1] = (bits & 2u) ? v.y : a[1];
+  a[2] = (bits & 4u) ? v.z : a[2];
+  a[3] = (bits & 8u) ? v.w : a[3];
+  return group;
 }
 
 // DIST: 0 normal (one Philox block per float4), 1 Student-t(3) (one block per element).
 // GRADBUF: gradients come from a caller buffer.  NORM: also write the sweep's squared drift.
 // TOPK: messages of this iteration may have to be applied.
-template <int DIST, bool GRADBUF, bool NORM, bool TOPK>
+// HISTA: also histogram the top 11 bits of the new rank keys per tensor, the first
+// radix pass of the next iteration's Top-K selection, while the values are in registers.
+template <int DIST, bool GRADBUF, bool NORM, bool TOPK, bool HISTA>
 __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   __shared__ double ws[4];
-  __shared__ float pv[TOPK ? 3 * kSweep : 1];   // LDS windows of the three patches
+  // LDS: the windows of the three patches; once those are consumed the same
+  // storage holds the key histogram
+  __shared__ __attribute__((aligned(16))) float pv[TOPK ? 3 * kSweep : 4];
   __shared__ uint32_t pm[96];
+  uint32_t* hA = reinterpret_cast<uint32_t*>(pv);
+  static_assert(!HISTA || (TOPK && 3 * kSweep >= kHistBins), "histogram must fit the patch windows");
   const uint32_t c = blockIdx.x / T.SW, sub = blockIdx.x % T.SW, r = blockIdx.y;
   const ChunkDesc cd = T.chunks[c];
   const uint32_t seg = r * T.L + cd.layer;
@@ -143,14 +146,15 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
         const uint32_t b0 = take_patch(pv, pm, ha);
         const uint32_t b1 = take_patch(pv + kSweep, pm + 32, la);
         const uint32_t b2 = take_patch(pv + 2 * kSweep, pm + 64, ra);
-        // Write back whole aligned groups of EVG_WB_LANES float4s (64 or 128 bytes) in
-        // which anything changed: scattered 16-byte writes cost far more in HBM than
-        // the few unchanged bytes a full line carries.
-        const uint32_t w0 = group_any(b0), w1 = group_any(b1), w2 = group_any(b2);
-        if (live && w0) st4(T.xhat + base + e, make_float4(ha[0], ha[1], ha[2], ha[3]));
-        if (live && w1) st4(T.mbox_l + base + e, make_float4(la[0], la[1], la[2], la[3]));
-        if (live && w2) st4(T.mbox_r + base + e, make_float4(ra[0], ra[1], ra[2], ra[3]));
+        if (live && b0) st4(T.xhat + base + e, make_float4(ha[0], ha[1], ha[2], ha[3]));
+        if (live && b1) st4(T.mbox_l + base + e, make_float4(la[0], la[1], la[2], la[3]));
+        if (live && b2) st4(T.mbox_r + base + e, make_float4(ra[0], ra[1], ra[2], ra[3]));
       }
+    }
+    if (HISTA) {
+      __syncthreads();                 // patches consumed by every thread
+      for (uint32_t b = threadIdx.x; b < (uint32_t)kHistBins; b += kThreads) hA[b] = 0;
+      __syncthreads();
     }
     if (live) {
       if (!GRADBUF) {
@@ -190,6 +194,19 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
       st4(T.x + base + e, make_float4(xa[0], xa[1], xa[2], xa[3]));
       st4(T.vel + base + e, make_float4(va[0], va[1], va[2], va[3]));
       if (NORM) drift_acc(acc, xa, ha, nv);
+      if (HISTA) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if ((uint32_t)i < nv) atomicAdd(&hA[rank_key(xa[i], ha[i], A.topk_key) >> 20], 1u);
+      }
+    }
+  }
+  if (HISTA && sub * kSweep < cd.len) {     // uniform
+    __syncthreads();
+    uint32_t* gh = T.hist + (size_t)seg * kHistBins;
+    for (uint32_t b = threadIdx.x; b < (uint32_t)kHistBins; b += kThreads) {
+      const uint32_t v = hA[b];
+      if (v) atomicAdd(&gh[b], v);
     }
   }
   if (NORM) {
@@ -216,23 +233,24 @@ hipError_t launch_norm(const Tables& t, uint32_t, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <bool NORM, bool TOPK>
+template <bool NORM, bool TOPK, bool HISTA>
 static void launch_update_v(const Tables& t, const StepArgs& a, uint32_t dist, uint32_t grad_mode,
                             hipStream_t s) {
   const dim3 grid(t.C * t.SW, t.P), block(kThreads);
-  if (grad_mode == 1) k_update<0, true, NORM, TOPK><<<grid, block, 0, s>>>(t, a);
-  else if (dist == 0) k_update<0, false, NORM, TOPK><<<grid, block, 0, s>>>(t, a);
-  else k_update<1, false, NORM, TOPK><<<grid, block, 0, s>>>(t, a);
+  if (grad_mode == 1) k_update<0, true, NORM, TOPK, HISTA><<<grid, block, 0, s>>>(t, a);
+  else if (dist == 0) k_update<0, false, NORM, TOPK, HISTA><<<grid, block, 0, s>>>(t, a);
+  else k_update<1, false, NORM, TOPK, HISTA><<<grid, block, 0, s>>>(t, a);
 }
 
 hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t, uint32_t dist,
                          uint32_t grad_mode, bool fused_norm, hipStream_t s) {
   if (a.topk_on) {
-    if (fused_norm) launch_update_v<true, true>(t, a, dist, grad_mode, s);
-    else launch_update_v<false, true>(t, a, dist, grad_mode, s);
+    if (fused_norm && a.hist_fused) launch_update_v<true, true, true>(t, a, dist, grad_mode, s);
+    else if (fused_norm) launch_update_v<true, true, false>(t, a, dist, grad_mode, s);
+    else launch_update_v<false, true, false>(t, a, dist, grad_mode, s);
   } else {
-    if (fused_norm) launch_update_v<true, false>(t, a, dist, grad_mode, s);
-    else launch_update_v<false, false>(t, a, dist, grad_mode, s);
+    if (fused_norm) launch_update_v<true, false, false>(t, a, dist, grad_mode, s);
+    else launch_update_v<false, false, false>(t, a, dist, grad_mode, s);
   }
   return hipGetLastError();
 }
