@@ -24,11 +24,15 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published peak, GB/s
-UPDATE_BYTES_PER_ELEM = 28     # reads x, mbox_l, mbox_r, vel, xhat; writes x, vel (fp32)
+# Algorithmic bytes of the update pass per element: reads x, mbox_l, mbox_r, vel,
+# xhat and writes x, vel (fp32) = 28; with Top-K it also reads the three messages
+# (8 rho per fired element) and scatters them into xhat and both mailboxes (12 rho).
+UPDATE_BYTES_PER_ELEM = 28
+UPDATE_TOPK_BYTES_PER_FIRED_ELEM_PER_RHO = 20
 
-# HBM traffic of one k_update launch on configuration 5, measured with
-# rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of
-# known size); see profiles/.  None until measured.
+# Average HBM bytes of one k_update launch, from two rocprofv3 --pmc runs of this
+# same command (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for
+# the library's plain copy kernel on a known size.  Source: profiles/.
 MEASURED_TRAFFIC_BYTES = {}
 
 
@@ -130,12 +134,13 @@ def main():
     if phases:
         ms_upd, n_upd = phases["update"]
         avg_ms = ms_upd / max(1, n_upd)
-        achieved = UPDATE_BYTES_PER_ELEM * elems / (avg_ms * 1e-3) / 1e9
+        upd_bytes = (UPDATE_BYTES_PER_ELEM + UPDATE_TOPK_BYTES_PER_FIRED_ELEM_PER_RHO * rho * f_topk) * elems
+        achieved = upd_bytes / (avg_ms * 1e-3) / 1e9
         out["roofline"] = {"kernel": "k_update", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
                            "avg_launch_ms": avg_ms, "launches": n_upd,
-                           "algorithmic_bytes_per_launch": UPDATE_BYTES_PER_ELEM * elems}
+                           "algorithmic_bytes_per_launch": upd_bytes}
         out["phase_ms_per_step"] = {p: ms / max(1, args.steps) for p, (ms, n) in phases.items()}
     ring.close()
     del ring
