@@ -33,7 +33,7 @@ UPDATE_TOPK_BYTES_PER_FIRED_ELEM_PER_RHO = 20
 # Average HBM bytes of one k_update launch, from two rocprofv3 --pmc runs of this
 # same command (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for
 # the library's plain copy kernel on a known size.  Source: profiles/.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"cfg5_resnet18_p64_topk10pct": 26.6e9}
 
 
 def cpu_baseline(inputs, w, seconds_hint=20.0):

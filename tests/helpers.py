@@ -25,7 +25,7 @@ def masked_mailboxes(ring_or_oracle, valid, numel):
 
 
 def lockstep(ring, orc, iters, *, grads=None, gpu_grads=None, sample_messages=32, seed=0,
-             check_every=None, progress=None):
+             check_every=None, progress=None, say=print):
     """Steps both sides through ``iters`` iterations.  After every iteration the
     decisions must agree exactly; a disagreement is tolerated only where both
     sides flag a near tie (|norm - delta| < 1e-6 delta), in which case the oracle
@@ -60,7 +60,7 @@ def lockstep(ring, orc, iters, *, grads=None, gpu_grads=None, sample_messages=32
             for name in ("x", "xhat", "vel"):
                 assert rel_err(ring.state(name), orc.state(name)) <= REL_TOL, (k, name)
         if progress and (k + 1) % progress == 0:
-            print(f"  lockstep iteration {k + 1}/{iters}", flush=True)
+            say(f"  lockstep iteration {k + 1}/{iters}")
     rep = {"near_tie_pairs": replayed, "bitwise": {}, "rel": {}}
     tb = orc.tables()
     gs = ring.stats(arrays=True)

@@ -7,8 +7,6 @@ whole; iteration 1: every tensor fires again -- a Top-K message where Top-K is o
 iteration 2: the first mixed iteration).  Longer full-size runs are checked through
 properties that hold at any size, and through Top-K selections recomputed for
 sampled tensors with a stable sort."""
-import sys
-
 import numpy as np
 import pytest
 
@@ -17,8 +15,13 @@ from paper_2103_07454_amd import inputs
 pytestmark = pytest.mark.gpu
 
 
-def say(msg):
-    print(msg, file=sys.__stderr__, flush=True)
+@pytest.fixture
+def say(capsys):
+    """Progress lines that reach the terminal even though pytest captures output."""
+    def emit(msg):
+        with capsys.disabled():
+            print(msg, flush=True)
+    return emit
 
 
 @pytest.fixture(scope="module")
@@ -30,7 +33,7 @@ def evg():
 
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("i,iters", [(3, 3), (4, 3), (5, 2)])
-def test_full_size_first_iterations_match_oracle(evg, oracle_mod, i, iters):
+def test_full_size_first_iterations_match_oracle(evg, oracle_mod, say, i, iters):
     from helpers import lockstep
     w = inputs.config(i)
     say(f"\n[full size cfg{i}] P={w.P} N={w.N} building")
@@ -38,7 +41,7 @@ def test_full_size_first_iterations_match_oracle(evg, oracle_mod, i, iters):
     ring = evg.Ring.from_workload(w, x0, mailbox_fill=float("nan"))
     orc = oracle_mod.Oracle.from_workload(w, np.ascontiguousarray(x0))
     del x0
-    rep = lockstep(ring, orc, iters, sample_messages=8, progress=1)
+    rep = lockstep(ring, orc, iters, sample_messages=8, progress=1, say=say)
     say(f"[full size cfg{i}] bitwise={rep['bitwise']} rel={rep['rel']}")
     assert all(rep["bitwise"].values())
     st = ring.stats()
@@ -46,7 +49,7 @@ def test_full_size_first_iterations_match_oracle(evg, oracle_mod, i, iters):
 
 
 @pytest.mark.timeout(600)
-def test_full_size_config5_properties_over_many_iterations(evg):
+def test_full_size_config5_properties_over_many_iterations(evg, say):
     """40 iterations of configuration 5 at full size on the GPU alone."""
     import torch
     w = inputs.config(5)
