@@ -120,8 +120,11 @@ __global__ __launch_bounds__(kThreads) void k_topk_pick(Tables T) {
   }
 }
 
+// Two sweeps (8 elements per thread) share one workgroup scan, so that twice as many
+// loads are in flight between barriers.
 template <int SWEEPS>
 __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
+  constexpr int STEP = SWEEPS >= 2 ? 2 : 1;
   __shared__ uint32_t h[kHistBins];
   __shared__ uint32_t ws[4];
   const uint32_t n = T.counts[1];
@@ -131,39 +134,55 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
     for (uint32_t b = threadIdx.x; b < (uint32_t)kHistBins; b += kThreads) h[b] = 0;
     __syncthreads();
     uint32_t run = 0;
-    for (int it = 0; it < SWEEPS; ++it) {       // uniform trip count: the scan needs every thread
-      const uint32_t e = it * kSweep + threadIdx.x * kLaneElems;
-      float xa[4] = {0.f, 0.f, 0.f, 0.f};
-      uint32_t key[4] = {0u, 0u, 0u, 0u}, take = 0;
-      if (e < wi.cd.len) {
-        const float4 x4 = ld4s(T.x + wi.base + e);
-        float4 h4 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (!A.topk_key) h4 = ld4s(T.xhat + wi.base + e);
-        xa[0] = x4.x; xa[1] = x4.y; xa[2] = x4.z; xa[3] = x4.w;
-        const float ha[4] = {h4.x, h4.y, h4.z, h4.w};
-        const uint32_t nv = wi.cd.len - e < 4u ? wi.cd.len - e : 4u;
+    for (int it = 0; it < SWEEPS; it += STEP) {   // uniform trip count: the scan needs every thread
+      float xa[STEP][4];
+      uint32_t key[STEP][4], take[STEP], e[STEP];
+      float4 x4[STEP], h4[STEP];
+#pragma unroll
+      for (int u = 0; u < STEP; ++u) {
+        e[u] = (it + u) * kSweep + threadIdx.x * kLaneElems;
+        x4[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        h4[u] = x4[u];
+        if (e[u] < wi.cd.len) {
+          x4[u] = ld4s(T.x + wi.base + e[u]);
+          if (!A.topk_key) h4[u] = ld4s(T.xhat + wi.base + e[u]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < STEP; ++u) {
+        take[u] = 0;
+        xa[u][0] = x4[u].x; xa[u][1] = x4[u].y; xa[u][2] = x4[u].z; xa[u][3] = x4[u].w;
+        const float ha[4] = {h4[u].x, h4[u].y, h4[u].z, h4[u].w};
+        const uint32_t nv = e[u] >= wi.cd.len ? 0u : (wi.cd.len - e[u] < 4u ? wi.cd.len - e[u] : 4u);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
+          key[u][q] = 0;
           if ((uint32_t)q < nv) {
-            key[q] = rank_key(xa[q], ha[q], A.topk_key);
-            const uint32_t kb = key[q] >> 20;
-            if (kb >= bin) take |= 1u << q;
-            if (kb == bin) atomicAdd(&h[(key[q] >> 9) & 2047u], 1u);
+            key[u][q] = rank_key(xa[u][q], ha[q], A.topk_key);
+            const uint32_t kb = key[u][q] >> 20;
+            if (kb >= bin) take[u] |= 1u << q;
+            if (kb == bin) atomicAdd(&h[(key[u][q] >> 9) & 2047u], 1u);
           }
         }
       }
+      // staged order = index order: all of sweep `it` precedes sweep `it + 1`
+      const uint32_t c0 = __popc(take[0]), c1 = STEP == 2 ? __popc(take[STEP - 1]) : 0u;
       uint32_t total;
-      uint32_t pos = run + block_excl_scan<4>(__popc(take), ws, &total);
+      const uint32_t ex = block_excl_scan<4>(c0 + (c1 << 16), ws, &total);
+      uint32_t pos[2] = {run + (ex & 0xFFFFu), run + (total & 0xFFFFu) + (ex >> 16)};
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if ((take >> q) & 1u) {
-          T.stage_key[wi.base + pos] = key[q];
-          T.stage_idx[wi.base + pos] = wi.cd.j0 + e + q;
-          T.stage_val[wi.base + pos] = xa[q];
-          ++pos;
+      for (int u = 0; u < STEP; ++u) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if ((take[u] >> q) & 1u) {
+            T.stage_key[wi.base + pos[u]] = key[u][q];
+            T.stage_idx[wi.base + pos[u]] = wi.cd.j0 + e[u] + q;
+            T.stage_val[wi.base + pos[u]] = xa[u][q];
+            ++pos[u];
+          }
         }
       }
-      run += total;
+      run += (total & 0xFFFFu) + (total >> 16);
     }
     if (threadIdx.x == 0) T.stage_n[wi.w] = run;
     __syncthreads();
