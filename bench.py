@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-timers", action="store_true")
+    ap.add_argument("--trigger-kind", type=int, default=0,
+                    help="0 = norm of the drift (default, the benchmark configurations); "
+                         "1 = difference of the norms")
     ap.add_argument("--diag-grad-buffer", action="store_true",
                     help="diagnostic only (not the named workload): gradients from a fixed device buffer")
     args = ap.parse_args()
@@ -81,8 +84,9 @@ def main():
 
     def make():
         if args.diag_grad_buffer:
-            return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk, grad_mode=evg.GRAD_BUFFER)
-        return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk)
+            return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk, grad_mode=evg.GRAD_BUFFER,
+                                          trigger_kind=args.trigger_kind)
+        return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk, trigger_kind=args.trigger_kind)
 
     ring = make()
     if args.diag_grad_buffer:
@@ -120,7 +124,8 @@ def main():
         "ms_per_step": 1e3 * dt / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name + ("+DIAG_GRAD_BUFFER" if args.diag_grad_buffer else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
+        "config": {"workload": w.name + ("+DIAG_GRAD_BUFFER" if args.diag_grad_buffer else "")
+                   + ("+NORM_DIFF_TRIGGER" if args.trigger_kind else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
                    "threshold": "adaptive" if w.thr_mode else "fixed", "topk_ppm": w.topk_ppm,
                    "chunk_elems": args.chunk or 8192,
                    "fraction_fired_full": f_full, "fraction_fired_topk": f_topk,
@@ -134,7 +139,10 @@ def main():
     if phases:
         ms_upd, n_upd = phases["update"]
         avg_ms = ms_upd / max(1, n_upd)
-        upd_bytes = (UPDATE_BYTES_PER_ELEM + UPDATE_TOPK_BYTES_PER_FIRED_ELEM_PER_RHO * rho * f_topk) * elems
+        per_elem = UPDATE_BYTES_PER_ELEM + UPDATE_TOPK_BYTES_PER_FIRED_ELEM_PER_RHO * rho * f_topk
+        if args.trigger_kind == 1 and not w.topk_ppm:
+            per_elem -= 4          # xhat is not read: its norm is a scalar per tensor
+        upd_bytes = per_elem * elems
         achieved = upd_bytes / (avg_ms * 1e-3) / 1e9
         out["roofline"] = {"kernel": "k_update", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

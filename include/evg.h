@@ -44,6 +44,7 @@ enum { EVG_KEY_ABS_DRIFT = 0, EVG_KEY_ABS_VALUE = 1 };
 enum { EVG_GRAD_SYNTH = 0, EVG_GRAD_BUFFER = 1 };
 enum { EVG_DIST_NORMAL = 0, EVG_DIST_STUDENT_T3 = 1 };
 enum { EVG_NORM_FUSED = 0, EVG_NORM_SEPARATE = 1 };
+enum { EVG_TRIGGER_DRIFT_NORM = 0, EVG_TRIGGER_NORM_DIFF = 1 };
 
 /* Synthetic gradients (they replace Algorithm B's "compute the local stochastic
  * gradient"): element j of tensor l of worker r at iteration k is
@@ -88,6 +89,10 @@ typedef struct {
                                    passes of their own read x and xhat                  */
   uint32_t chunk_elems;         /* work granule of the send kernels: 0 (= 8192), 1024,
                                    2048, 4096 or 8192 elements; no tensor shares one    */
+  uint32_t trigger_kind;        /* EVG_TRIGGER_DRIFT_NORM: test || x - xhat || (the formula of
+                                   Section 4); EVG_TRIGGER_NORM_DIFF: test | ||x|| - ||xhat|| |
+                                   (the wording of Section 4: "when the norm has changed by
+                                   some threshold"); Eq. 3 then uses the same quantity      */
   evg_synth synth;
   /* DEVICE arenas owned by the caller, each P * evg_padded_numel() floats,
    * 16-byte aligned, non-overlapping, alive until evg_destroy.  Worker r's

@@ -203,6 +203,7 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   if (cfg->topk_key > EVG_KEY_ABS_VALUE) return fail(EVG_ERR_INVALID, "unknown topk_key %u", cfg->topk_key);
   if (cfg->grad_mode > EVG_GRAD_BUFFER) return fail(EVG_ERR_INVALID, "unknown grad_mode %u", cfg->grad_mode);
   if (cfg->norm_mode > EVG_NORM_SEPARATE) return fail(EVG_ERR_INVALID, "unknown norm_mode %u", cfg->norm_mode);
+  if (cfg->trigger_kind > EVG_TRIGGER_NORM_DIFF) return fail(EVG_ERR_INVALID, "unknown trigger_kind %u", cfg->trigger_kind);
   const uint32_t ce = cfg->chunk_elems ? cfg->chunk_elems : 8192u;
   if (ce != 1024 && ce != 2048 && ce != 4096 && ce != 8192)
     return fail(EVG_ERR_INVALID, "chunk_elems must be 0, 1024, 2048, 4096 or 8192");
@@ -324,6 +325,10 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   t.chunks = d_chunks;
   t.layers = d_layers;
   TRY_OR_FREE(c->dalloc(&t.partials, P * C * t.SW, true));
+  if (cfg->trigger_kind == EVG_TRIGGER_NORM_DIFF) {
+    TRY_OR_FREE(c->dalloc(&t.partials_hat, P * C * t.SW, true));
+    TRY_OR_FREE(c->dalloc(&t.xhat_sq, S, true));
+  }
   TRY_OR_FREE(c->dalloc(&t.delta, S, false));
   TRY_OR_FREE(c->dalloc(&t.last_norm, S, true));
   TRY_OR_FREE(c->dalloc(&t.delta_before, S, true));
@@ -367,7 +372,7 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   HIP_OR_FREE(hipMemsetAsync(t.last_event, 0xFF, S * sizeof(int32_t), c->stream));
   HIP_OR_FREE(hipMemcpyAsync(t.xhat, t.x, arena_bytes, hipMemcpyDeviceToDevice, c->stream));
   HIP_OR_FREE(hipMemsetAsync(t.vel, 0, arena_bytes, c->stream));
-  HIP_OR_FREE(launch_norm(t, ce, c->stream));
+  HIP_OR_FREE(launch_norm(t, cfg->trigger_kind == EVG_TRIGGER_NORM_DIFF, c->stream));
   HIP_OR_FREE(hipStreamSynchronize(c->stream));   // host staging buffers above go out of scope
 #undef TRY_OR_FREE
 #undef HIP_OR_FREE
@@ -395,6 +400,9 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   a.topk_on = g.topk_ppm ? 1u : 0u;
   a.topk_key = g.topk_key;
   a.hist_fused = (g.topk_ppm && g.norm_mode == EVG_NORM_FUSED) ? 1u : 0u;
+  const bool norm_diff = g.trigger_kind == EVG_TRIGGER_NORM_DIFF;
+  // fused + whole-tensor sends: xhat's norm is a scalar per tensor and xhat is never read
+  a.norm_src = !norm_diff ? 0u : (g.norm_mode == EVG_NORM_FUSED && !g.topk_ppm) ? 1u : 2u;
   a.key0 = (uint32_t)g.synth.seed;
   a.key1 = (uint32_t)(g.synth.seed >> 32);
   a.decay_pow = std::pow(g.synth.decay, (double)iter);
@@ -410,7 +418,7 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   evg_status st;
   if (!fused) {
     Phase ph(c, EVG_PH_NORM);
-    HIP_TRY(launch_norm(t, c->chunk_elems, c->stream));
+    HIP_TRY(launch_norm(t, norm_diff, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
   }
   {
@@ -439,7 +447,8 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   }
   {
     Phase ph(c, EVG_PH_UPDATE);
-    HIP_TRY(launch_update(t, a, c->chunk_elems, g.synth.dist, g.grad_mode, fused, c->stream));
+    const int norm = !fused ? 0 : !norm_diff ? 1 : g.topk_ppm ? 3 : 2;
+    HIP_TRY(launch_update(t, a, g.synth.dist, g.grad_mode, norm, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
   }
   c->last_iter = (int64_t)iter;

@@ -34,7 +34,11 @@ struct Tables {
   const ChunkDesc* chunks;
   const LayerDesc* layers;
   float* x; float* xhat; float* mbox_l; float* mbox_r; float* vel;
-  double* partials;        // [P*C*SW] sum of squared drift per 1024-element sweep of a chunk
+  double* partials;        // [P*C*SW] per 1024-element sweep of a chunk: sum of squared drift, or
+                           // of squared x when the trigger compares norms
+  double* partials_hat;    // [P*C*SW] sum of squared xhat (norm-difference trigger only)
+  double* xhat_sq;         // [S] squared norm of what was last sent, kept as a scalar when whole
+                           // tensors are sent (norm-difference trigger only)
   float* delta; float* last_norm; float* delta_before;
   int32_t* last_event;
   uint8_t* valid_l; uint8_t* valid_r; uint8_t* fired; uint8_t* near_tie;
@@ -69,6 +73,9 @@ struct StepArgs {
   uint32_t force_first;
   uint32_t topk_on;
   uint32_t topk_key;
+  uint32_t norm_src;       // what k_trigger finds: 0 squared drift in partials; 1 squared x in
+                           // partials, squared xhat in xhat_sq once a tensor has sent; 2 squared x
+                           // and squared xhat in partials / partials_hat
   uint32_t hist_fused;     // the update pass of the previous iteration already built pass A's histograms
   uint32_t key0, key1;
   double decay_pow;        // decay^k
@@ -77,9 +84,10 @@ struct StepArgs {
 };
 
 // launchers (each enqueues on the stream and returns the launch status)
-hipError_t launch_norm(const Tables& t, uint32_t chunk_elems, hipStream_t s);
-hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t dist,
-                         uint32_t grad_mode, bool fused_norm, hipStream_t s);
+hipError_t launch_norm(const Tables& t, bool norm_diff, hipStream_t s);
+// norm: 0 no norm work, 1 squared drift, 2 squared x, 3 squared x and squared xhat
+hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t dist, uint32_t grad_mode,
+                         int norm, hipStream_t s);
 hipError_t launch_trigger(const Tables& t, const StepArgs& a, hipStream_t s);
 hipError_t launch_scan(const Tables& t, hipStream_t s);
 hipError_t launch_expand(const Tables& t, hipStream_t s);

@@ -19,12 +19,26 @@ __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
   const LayerDesc ld = T.layers[l];
   const double* part = T.partials + ((size_t)r * T.C + ld.chunk0) * T.SW;
   const uint32_t np = ld.nchunks * T.SW;
-  double acc = 0.0;
+  double acc = 0.0, acc_hat = 0.0;
   for (uint32_t i = lane_id(); i < np; i += 64) acc += part[i];
   acc = wave_sum(acc);
+  // norm-difference trigger: the squared norm of xhat comes from the arena sums, or, where
+  // whole tensors are sent, from the scalar kept at the tensor's last event
+  const bool hat_sums = A.norm_src == 2 || (A.norm_src == 1 && T.last_event[seg] < 0);
+  if (hat_sums) {
+    const double* ph = T.partials_hat + ((size_t)r * T.C + ld.chunk0) * T.SW;
+    for (uint32_t i = lane_id(); i < np; i += 64) acc_hat += ph[i];
+    acc_hat = wave_sum(acc_hat);
+  }
   if (lane_id() != 0) return;
 
-  const float d = (float)sqrt(acc);
+  float d;
+  if (A.norm_src == 0) {
+    d = (float)sqrt(acc);
+  } else {
+    if (!hat_sums) acc_hat = T.xhat_sq[seg];
+    d = __builtin_fabsf((float)sqrt(acc) - (float)sqrt(acc_hat));
+  }
   const float dl = T.delta[seg];
   T.last_norm[seg] = d;
   T.delta_before[seg] = dl;
@@ -56,6 +70,7 @@ __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
       }
     }
     T.last_event[seg] = (int32_t)A.k;
+    if (A.norm_src == 1) T.xhat_sq[seg] = acc;    // the whole tensor is sent: xhat becomes x
     // a tensor's first message has nothing to patch on the receiving side: send it whole
     if (!A.topk_on || khat < 0) { code = 1; T.ev_full[seg] += 1; }
     else { code = 2; T.ev_topk[seg] += 1; }

@@ -31,21 +31,36 @@ __device__ __forceinline__ void drift_acc(double& acc, const float x[4], const f
   }
 }
 
+// Sum of squares of the first nv lanes, added in lane order.
+__device__ __forceinline__ void square_acc(double& acc, const float x[4], uint32_t nv) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if ((uint32_t)i < nv) acc += (double)x[i] * (double)x[i];
+}
+
+// NORMDIFF: the trigger compares ||x|| with ||xhat||: two sums instead of the drift's.
+template <bool NORMDIFF>
 __global__ __launch_bounds__(kThreads) void k_norm(Tables T) {
   __shared__ double ws[4];
   const uint32_t c = blockIdx.x / T.SW, sub = blockIdx.x % T.SW, r = blockIdx.y;
   const ChunkDesc cd = T.chunks[c];
   const size_t base = (size_t)r * T.Npad + cd.off;
   const uint32_t e = sub * kSweep + threadIdx.x * kLaneElems;
-  double acc = 0.0;
+  double acc = 0.0, acc_hat = 0.0;
   if (e < cd.len) {
     const float4 x4 = ld4(T.x + base + e), h4 = ld4(T.xhat + base + e);
     const float xa[4] = {x4.x, x4.y, x4.z, x4.w}, ha[4] = {h4.x, h4.y, h4.z, h4.w};
     const uint32_t nv = cd.len - e < 4u ? cd.len - e : 4u;
-    drift_acc(acc, xa, ha, nv);
+    if (NORMDIFF) { square_acc(acc, xa, nv); square_acc(acc_hat, ha, nv); }
+    else drift_acc(acc, xa, ha, nv);
   }
+  const size_t slot = ((size_t)r * T.C + c) * T.SW + sub;
   const double total = block_sum(acc, ws);
-  if (threadIdx.x == 0) T.partials[((size_t)r * T.C + c) * T.SW + sub] = total;
+  if (threadIdx.x == 0) T.partials[slot] = total;
+  if (NORMDIFF) {
+    const double total_hat = block_sum(acc_hat, ws);
+    if (threadIdx.x == 0) T.partials_hat[slot] = total_hat;
+  }
 }
 
 // One source of a sparse patch for this workgroup's 1024-element window: the slice
@@ -93,11 +108,13 @@ __device__ __forceinline__ uint32_t take_patch(const float* pv, const uint32_t* 
 }
 
 // DIST: 0 normal (one Philox block per float4), 1 Student-t(3) (one block per element).
-// GRADBUF: gradients come from a caller buffer.  NORM: also write the sweep's squared drift.
+// GRADBUF: gradients come from a caller buffer.
+// NORM: what the pass accumulates for the next trigger test: 0 nothing, 1 the sweep's squared
+// drift, 2 its squared x (xhat is then not read at all), 3 its squared x and squared xhat.
 // TOPK: messages of this iteration may have to be applied.
 // HISTA: also histogram the top 11 bits of the new rank keys per tensor, the first
 // radix pass of the next iteration's Top-K selection, while the values are in registers.
-template <int DIST, bool GRADBUF, bool NORM, bool TOPK, bool HISTA>
+template <int DIST, bool GRADBUF, int NORM, bool TOPK, bool HISTA>
 __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   __shared__ double ws[4];
   // LDS: the windows of the three patches; once those are consumed the same
@@ -114,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   const float third = 0.333333343f;   // (float)(1/3): the ring's mixing weight
   const uint32_t e = sub * kSweep + threadIdx.x * kLaneElems;
   const bool live = e < cd.len;
-  double acc = 0.0;
+  double acc = 0.0, acc_hat = 0.0;
   if (sub * kSweep < cd.len) {        // uniform: this sweep holds elements
     float xa[4] = {0.f, 0.f, 0.f, 0.f}, va[4] = {0.f, 0.f, 0.f, 0.f};
     float la[4] = {0.f, 0.f, 0.f, 0.f}, ra[4] = {0.f, 0.f, 0.f, 0.f}, ha[4] = {0.f, 0.f, 0.f, 0.f};
@@ -125,7 +142,7 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
       va[0] = v4.x; va[1] = v4.y; va[2] = v4.z; va[3] = v4.w;
       if (vl) { const float4 t = ld4(T.mbox_l + base + e); la[0] = t.x; la[1] = t.y; la[2] = t.z; la[3] = t.w; }
       if (vr) { const float4 t = ld4(T.mbox_r + base + e); ra[0] = t.x; ra[1] = t.y; ra[2] = t.z; ra[3] = t.w; }
-      if (NORM || TOPK) { const float4 t = ld4(T.xhat + base + e); ha[0] = t.x; ha[1] = t.y; ha[2] = t.z; ha[3] = t.w; }
+      if (NORM == 1 || NORM == 3 || TOPK) { const float4 t = ld4(T.xhat + base + e); ha[0] = t.x; ha[1] = t.y; ha[2] = t.z; ha[3] = t.w; }
       if (GRADBUF) { const float4 t = ld4(A.grad + base + e); g[0] = t.x; g[1] = t.y; g[2] = t.z; g[3] = t.w; }
     }
     if (TOPK) {
@@ -193,7 +210,9 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
       }
       st4(T.x + base + e, make_float4(xa[0], xa[1], xa[2], xa[3]));
       st4(T.vel + base + e, make_float4(va[0], va[1], va[2], va[3]));
-      if (NORM) drift_acc(acc, xa, ha, nv);
+      if (NORM == 1) drift_acc(acc, xa, ha, nv);
+      if (NORM >= 2) square_acc(acc, xa, nv);
+      if (NORM == 3) square_acc(acc_hat, ha, nv);
       if (HISTA) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -210,8 +229,13 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
     }
   }
   if (NORM) {
+    const size_t slot = ((size_t)r * T.C + c) * T.SW + sub;
     const double total = block_sum(acc, ws);
-    if (threadIdx.x == 0) T.partials[((size_t)r * T.C + c) * T.SW + sub] = total;
+    if (threadIdx.x == 0) T.partials[slot] = total;
+    if (NORM == 3) {
+      const double total_hat = block_sum(acc_hat, ws);
+      if (threadIdx.x == 0) T.partials_hat[slot] = total_hat;
+    }
   }
 }
 
@@ -228,12 +252,14 @@ __global__ __launch_bounds__(kThreads) void k_average(Tables T, float* out) {
   st4(out + q * 4, make_float4((float)(a0 / p), (float)(a1 / p), (float)(a2 / p), (float)(a3 / p)));
 }
 
-hipError_t launch_norm(const Tables& t, uint32_t, hipStream_t s) {
-  k_norm<<<dim3(t.C * t.SW, t.P), dim3(kThreads), 0, s>>>(t);
+hipError_t launch_norm(const Tables& t, bool norm_diff, hipStream_t s) {
+  const dim3 grid(t.C * t.SW, t.P), block(kThreads);
+  if (norm_diff) k_norm<true><<<grid, block, 0, s>>>(t);
+  else k_norm<false><<<grid, block, 0, s>>>(t);
   return hipGetLastError();
 }
 
-template <bool NORM, bool TOPK, bool HISTA>
+template <int NORM, bool TOPK, bool HISTA>
 static void launch_update_v(const Tables& t, const StepArgs& a, uint32_t dist, uint32_t grad_mode,
                             hipStream_t s) {
   const dim3 grid(t.C * t.SW, t.P), block(kThreads);
@@ -242,15 +268,18 @@ static void launch_update_v(const Tables& t, const StepArgs& a, uint32_t dist, u
   else k_update<1, false, NORM, TOPK, HISTA><<<grid, block, 0, s>>>(t, a);
 }
 
-hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t, uint32_t dist,
-                         uint32_t grad_mode, bool fused_norm, hipStream_t s) {
+hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t dist, uint32_t grad_mode,
+                         int norm, hipStream_t s) {
   if (a.topk_on) {
-    if (fused_norm && a.hist_fused) launch_update_v<true, true, true>(t, a, dist, grad_mode, s);
-    else if (fused_norm) launch_update_v<true, true, false>(t, a, dist, grad_mode, s);
-    else launch_update_v<false, true, false>(t, a, dist, grad_mode, s);
+    if (norm == 1 && a.hist_fused) launch_update_v<1, true, true>(t, a, dist, grad_mode, s);
+    else if (norm == 3 && a.hist_fused) launch_update_v<3, true, true>(t, a, dist, grad_mode, s);
+    else if (norm == 0) launch_update_v<0, true, false>(t, a, dist, grad_mode, s);
+    else return hipErrorInvalidValue;
   } else {
-    if (fused_norm) launch_update_v<true, false, false>(t, a, dist, grad_mode, s);
-    else launch_update_v<false, false, false>(t, a, dist, grad_mode, s);
+    if (norm == 0) launch_update_v<0, false, false>(t, a, dist, grad_mode, s);
+    else if (norm == 1) launch_update_v<1, false, false>(t, a, dist, grad_mode, s);
+    else if (norm == 2) launch_update_v<2, false, false>(t, a, dist, grad_mode, s);
+    else return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }

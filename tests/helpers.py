@@ -25,7 +25,7 @@ def masked_mailboxes(ring_or_oracle, valid, numel):
 
 
 def lockstep(ring, orc, iters, *, grads=None, gpu_grads=None, sample_messages=32, seed=0,
-             check_every=None, progress=None, say=print):
+             check_every=None, progress=None, say=print, norm_rtol=2e-7):
     """Steps both sides through ``iters`` iterations.  After every iteration the
     decisions must agree exactly; a disagreement is tolerated only where both
     sides flag a near tie (|norm - delta| < 1e-6 delta), in which case the oracle
@@ -45,8 +45,9 @@ def lockstep(ring, orc, iters, *, grads=None, gpu_grads=None, sample_messages=32
                                f"delta {od['delta_before'][bad][:5]}")
         replayed += int(((od["near_tie"] != 0) & (gd["near_tie"] != 0)).sum())
         # norms agree to summation-order rounding; thresholds likewise
-        np.testing.assert_allclose(gd["norm"], od["norm"], rtol=2e-7, atol=1e-37, equal_nan=True)
-        np.testing.assert_allclose(gd["delta_before"], od["delta_before"], rtol=4e-7, atol=1e-37)
+        if norm_rtol is not None:
+            np.testing.assert_allclose(gd["norm"], od["norm"], rtol=norm_rtol, atol=1e-37, equal_nan=True)
+            np.testing.assert_allclose(gd["delta_before"], od["delta_before"], rtol=2 * norm_rtol, atol=1e-37)
         if sample_messages:
             rs, ls = np.nonzero(gd["fired"] == 2)
             if rs.size:
@@ -68,7 +69,8 @@ def lockstep(ring, orc, iters, *, grads=None, gpu_grads=None, sample_messages=32
     assert np.array_equal(gs["events_full_rl"], tb["events_full"])
     assert np.array_equal(gs["events_topk_rl"], tb["events_topk"])
     assert np.array_equal(gs["last_event_iter"], tb["last_event_iter"])
-    np.testing.assert_allclose(gs["delta"], tb["delta"], rtol=4e-7, atol=1e-37)
+    if norm_rtol is not None:
+        np.testing.assert_allclose(gs["delta"], tb["delta"], rtol=2 * norm_rtol, atol=1e-37)
     tot = orc.totals()
     for key in ("events_total", "value_words", "index_words", "bytes_sent", "nonfinite_norms", "iters"):
         assert gs[key] == tot[key], (key, gs[key], tot[key])

@@ -160,6 +160,20 @@ def test_buffer_gradients_and_history(evg, oracle_mod):
     assert all(rep["bitwise"].values())
 
 
+@pytest.mark.parametrize("mode", ["whole_fused", "topk_fused", "whole_separate", "topk_separate"])
+def test_norm_difference_trigger(evg, oracle_mod, mode):
+    """Trigger on | ||x|| - ||xhat|| | (the wording of Section 4) instead of || x - xhat ||."""
+    from helpers import lockstep
+    w = ragged(topk_ppm=100_000 if "topk" in mode else 0)
+    gpu = dict(norm_mode=evg.NORM_SEPARATE if "separate" in mode else evg.NORM_FUSED)
+    ring, orc = pair(evg, oracle_mod, w, gpu=gpu, trigger_kind=1)
+    rep = lockstep(ring, orc, w.iters, norm_rtol=None)
+    note(f"norm-difference/{mode}", rep)
+    st = ring.stats()
+    assert w.P * w.L * 2 <= st["events_total"] < st["regular_events"]
+    assert rep["rel"]["x"] <= 1e-5
+
+
 def test_separate_norm_pass_matches_fused(evg):
     w = ragged(topk_ppm=100_000)
     a = evg.Ring.from_workload(w)

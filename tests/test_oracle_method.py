@@ -441,3 +441,60 @@ def test_rejects_bad_configurations(oracle_mod):
     o.step(0, grad=np.zeros((3, 4), np.float32))
     with pytest.raises(RuntimeError):
         o.step(0, grad=np.zeros((3, 4), np.float32))   # iterations must increase
+
+
+# --------------------------------------------------------------------------
+# the other reading of Section 4's wording: the norm itself has to change
+# --------------------------------------------------------------------------
+def test_norm_difference_trigger_ignores_rotations(oracle_mod):
+    """A tensor that turns from (1,0) to (0,1) has moved by sqrt(2) but its norm has not
+    changed: the drift-norm trigger fires, the norm-difference trigger stays silent until
+    the length changes."""
+    P = 3
+    x0 = np.tile(np.array([[1.0, 0.0]], np.float32), (P, 1))
+    mk = lambda kind: oracle_mod.Oracle(x0, np.array([2], np.uint64), None, lr=1.0, momentum=0.0,
+                                        thr_mode=0, thr_fixed=0.5, grad_mode=1, trigger_kind=kind)
+    g0 = np.tile(np.array([[1.0, -1.0]], np.float32), (P, 1))       # (1,0) -> (0,1)
+    zero = np.zeros_like(g0)
+    a, b = mk(0), mk(1)
+    for o in (a, b):
+        o.step(0, grad=g0)
+        assert o.decisions()["fired"].all()                        # forced first event
+        assert np.array_equal(o.state("x"), np.tile(np.array([[0.0, 1.0]], np.float32), (P, 1)))
+        o.step(1, grad=zero)
+    da, db = a.decisions(), b.decisions()
+    assert da["fired"].all() and abs(da["norm"][0, 0] - math.sqrt(2)) < 1e-6
+    assert not db["fired"].any() and db["norm"][0, 0] == 0.0
+    # b: x = (0,1) + 2/3 ((1,0) - (0,1)) = (2/3, 1/3); push it out to length 2
+    x = b.state("x")[0].astype(np.float64)
+    np.testing.assert_allclose(x, [2 / 3, 1 / 3], atol=1e-6)
+    b.step(2, grad=zero)            # |x| = sqrt(5)/3 = 0.745: changed by 0.255 < 0.5, still silent
+    d = b.decisions()
+    assert not d["fired"].any() and abs(d["norm"][0, 0] - (1 - math.sqrt(5) / 3)) < 1e-6
+    x = b.state("x")[0].astype(np.float64)
+    g = np.tile((x + 2 / 3 * (np.array([1.0, 0.0]) - x) - np.array([2.0, 0.0]))[None, :], (P, 1)).astype(np.float32)
+    b.step(3, grad=g)               # lands on (2, 0)
+    b.step(4, grad=zero)
+    d = b.decisions()
+    assert d["fired"].all() and abs(d["norm"][0, 0] - 1.0) < 1e-5   # | 2 - 1 |
+
+
+def test_norm_difference_trigger_adaptive_and_topk_invariants(oracle_mod):
+    w = small_workload(topk_ppm=200_000)
+    o = oracle_mod.Oracle.from_workload(w, trigger_kind=1)
+    numel = w.layer_numel.astype(np.int64)
+    off = np.concatenate([[0], np.cumsum(numel)])
+    for k in range(25):
+        x_prev, h_prev = o.state("x"), o.state("xhat")
+        o.step(k)
+        d = o.decisions()
+        for r in range(w.P):
+            for l in range(w.L):
+                sl = slice(off[l], off[l + 1])
+                nx = np.float32(math.sqrt(float(np.dot(x_prev[r, sl].astype(np.float64), x_prev[r, sl].astype(np.float64)))))
+                nh = np.float32(math.sqrt(float(np.dot(h_prev[r, sl].astype(np.float64), h_prev[r, sl].astype(np.float64)))))
+                assert abs(d["norm"][r, l] - abs(float(nx) - float(nh))) <= 2e-6 * float(nx)
+                if d["fired"][r, l] == 0:
+                    assert d["norm"][r, l] < d["delta_before"][r, l]
+    t = o.totals()
+    assert w.P * w.L * 2 <= t["events_total"] < w.P * w.L * 25
