@@ -98,6 +98,7 @@ class Oracle:
                  force_first=1, topk_ppm=0, topk_key=0, trigger_kind=0, grad_mode=0,
                  seed=0, dist=0, fan_in_scaling=0, sigma0=0.0, decay=1.0,
                  spike_prob=0.0, spike_gain=1.0):
+        self._h = None
         x0 = np.ascontiguousarray(x0, dtype=np.float32)
         self.P, self.N = x0.shape
         self._numel = np.ascontiguousarray(layer_numel, dtype=np.uint64)

@@ -1,0 +1,119 @@
+"""GPU parity on degenerate and extreme shapes: single elements, many workers, keys
+with massive ties that straddle chunk boundaries, non-finite drift."""
+import numpy as np
+import pytest
+
+from paper_2103_07454_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def evg():
+    from paper_2103_07454_amd import evg as m
+    m.lib()
+    return m
+
+
+def spec(sizes):
+    return [inputs.TensorSpec(f"t{i}", (n,), max(1, n // 3), "weight") for i, n in enumerate(sizes)]
+
+
+def run(evg, oracle_mod, w, iters, gpu=None, **over):
+    from helpers import lockstep
+    x0 = inputs.replicate(w.x0(), w.P)
+    ring = evg.Ring.from_workload(w, x0, mailbox_fill=float("nan"), **over, **(gpu or {}))
+    orc = oracle_mod.Oracle.from_workload(w, x0, **over)
+    rep = lockstep(ring, orc, iters, sample_messages=64)
+    assert all(rep["bitwise"].values()), rep
+    return ring, orc
+
+
+@pytest.mark.parametrize("topk", [0, 1, 500_000, 1_000_000])
+def test_single_element_tensors(evg, oracle_mod, topk):
+    w = inputs.Workload("one", 3, spec([1]), 30, sigma0=0.1, decay=0.95, topk_ppm=topk, seed=5)
+    run(evg, oracle_mod, w, 30)
+    w = inputs.Workload("ones", 4, spec([1, 1, 2, 1, 3]), 30, sigma0=0.1, decay=0.95, topk_ppm=topk, seed=6)
+    run(evg, oracle_mod, w, 30)
+
+
+def test_many_workers_small_tensors(evg, oracle_mod):
+    w = inputs.Workload("wide_ring", 301, spec([5, 130, 1025, 7]), 25, sigma0=0.05, decay=0.97,
+                        topk_ppm=150_000, seed=8)
+    ring, _ = run(evg, oracle_mod, w, 25)
+    assert ring.stats()["events_total"] > 301 * 4 * 2
+
+
+@pytest.mark.parametrize("chunk", [1024, 8192])
+def test_one_large_tensor_many_chunks(evg, oracle_mod, chunk):
+    for ppm in (1, 1000, 333_333):
+        w = inputs.Workload("big", 3, spec([300_001, 3]), 12, sigma0=0.05, decay=0.97, topk_ppm=ppm, seed=9)
+        run(evg, oracle_mod, w, 12, gpu=dict(chunk_elems=chunk))
+
+
+@pytest.mark.parametrize("chunk", [1024, 4096])
+def test_ties_across_chunks(evg, oracle_mod, chunk):
+    """Gradients quantised to three values: drift keys take a handful of distinct values,
+    so the threshold key is shared by thousands of elements spread over many chunks and
+    the lowest-index rule decides almost every winner."""
+    import torch
+    from helpers import lockstep
+    w = inputs.Workload("ties", 4, spec([50_000, 4097, 9]), 16, topk_ppm=100_000, seed=10,
+                        thr_mode=inputs.THR_FIXED, thr_fixed=0.0)
+    x0 = inputs.replicate(w.x0(), w.P)
+    ring = evg.Ring.from_workload(w, x0, grad_mode=1, lr=0.5, momentum=0.0, chunk_elems=chunk)
+    orc = oracle_mod.Oracle.from_workload(w, x0, grad_mode=1, lr=0.5, momentum=0.0)
+    keep = []
+
+    def host(k):
+        g = np.sign(inputs.random_grads(w.P, w.N, 40 + k)) * np.float32(0.25)
+        g[np.abs(inputs.random_grads(w.P, w.N, 140 + k)) < 0.6] = 0
+        return g.astype(np.float32)
+
+    def dev(k):
+        keep.append(torch.from_numpy(ring.layout.pad(host(k))).cuda())
+        return keep[-1]
+
+    rep = lockstep(ring, orc, 16, grads=host, gpu_grads=dev, sample_messages=64)
+    assert all(rep["bitwise"].values())
+
+
+def test_nonfinite_drift_is_counted_and_never_fires(evg, oracle_mod):
+    import torch
+    from helpers import lockstep
+    w = inputs.Workload("nan", 3, spec([2000, 8]), 4, thr_mode=inputs.THR_FIXED, thr_fixed=0.5, force_first=0)
+    x0 = inputs.replicate(w.x0(), w.P)
+    ring = evg.Ring.from_workload(w, x0, grad_mode=1, lr=1.0, momentum=0.0)
+    orc = oracle_mod.Oracle.from_workload(w, x0, grad_mode=1, lr=1.0, momentum=0.0)
+    g = np.zeros((w.P, w.N), np.float32)
+    g[1, 17] = np.nan
+    g[2, 2003] = np.inf
+    bufs = [torch.from_numpy(ring.layout.pad(g)).cuda(), torch.zeros_like(ring.x)]
+    seen = []
+    for k in range(3):
+        ring.step(k, bufs[min(k, 1)])
+        orc.step(k, grad=g if k == 0 else np.zeros_like(g))
+        gd, od = ring.decisions(), orc.decisions()
+        assert np.array_equal(gd["fired"], od["fired"])
+        assert np.array_equal(np.isnan(gd["norm"]), np.isnan(od["norm"]))
+        assert np.array_equal(np.isinf(gd["norm"]), np.isinf(od["norm"]))
+        seen.append(gd)
+    # iteration 1 sees the damage done by iteration 0's gradients
+    assert seen[1]["fired"][1, 0] == 0 and np.isnan(seen[1]["norm"][1, 0])      # NaN never fires
+    assert seen[1]["fired"][2, 1] == 1 and np.isinf(seen[1]["norm"][2, 1])      # +inf >= 0.5 does
+    # ... after which xhat holds the infinity too: inf - inf = NaN, silent again
+    assert seen[2]["fired"][2, 1] == 0 and np.isnan(seen[2]["norm"][2, 1])
+    # iteration 1: two tests; iteration 2: those two again plus worker 2's two neighbours,
+    # which averaged the infinity in
+    assert ring.stats()["nonfinite_norms"] == orc.totals()["nonfinite_norms"] == 6
+
+
+def test_first_event_later_than_iteration_zero(evg, oracle_mod):
+    """No forced event and a positive starting threshold: tensors send for the first time
+    at different iterations; each first message must be whole even with Top-K on."""
+    w = inputs.Workload("late", 5, spec([3000, 40, 5000]), 40, sigma0=0.02, fan_in_scaling=0, decay=1.0,
+                        topk_ppm=50_000, delta_init=0.2, force_first=0, seed=12)
+    ring, orc = run(evg, oracle_mod, w, 40)
+    st = ring.stats(arrays=True)
+    assert (st["events_full_rl"] <= 1).all() and st["events_topk"] > 0
+    assert (st["events_full_rl"][:, [0, 2]] == 1).all()      # the large tensors did start sending
