@@ -201,6 +201,8 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
   return __popcll(mask & ((1ull << lane_id()) - 1ull));
 }
 
+constexpr int kBatch = 4;    // 64-entry groups loaded together by a wavefront, to overlap their latency
+
 // Bits 8..0 of the staged keys that carry the 22-bit prefix found so far.  Matches are
 // rare (a 2^-22 slice of the key range), so they go straight to the tensor's histogram,
 // one atomic per distinct value per 64 entries.
@@ -210,18 +212,25 @@ __global__ __launch_bounds__(kThreads) void k_topk_hist_low(Tables T) {
     const WorkItem wi = work_item(T, i);
     const uint32_t prefix = T.sel_prefix[wi.seg], ns = T.stage_n[wi.w];
     uint32_t* gh = T.hist + (size_t)wi.seg * kHistBins;
-    for (uint32_t q0 = 0; q0 < ns; q0 += 64) {
-      const uint32_t q = q0 + lane_id();
-      const uint32_t key = q < ns ? T.stage_key[wi.base + q] : 0u;
-      bool pending = q < ns && (key >> 9) == prefix;
-      uint64_t todo = __ballot(pending);
-      while (todo) {                                  // uniform: every lane sees the same mask
-        const uint32_t leader = __ffsll((unsigned long long)todo) - 1;
-        const uint32_t v = __shfl(key & 511u, leader, 64);
-        const uint64_t same = __ballot(pending && (key & 511u) == v);
-        if (lane_id() == leader) atomicAdd(&gh[v], (uint32_t)__popcll(same));
-        if ((same >> lane_id()) & 1ull) pending = false;
-        todo &= ~same;
+    for (uint32_t q0 = 0; q0 < ns; q0 += 64 * kBatch) {
+      uint32_t key[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const uint32_t q = q0 + u * 64 + lane_id();
+        key[u] = q < ns ? T.stage_key[wi.base + q] : 0xFFFFFFFFu;   // no key has bit 31: never matches
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        bool pending = (key[u] >> 9) == prefix;
+        uint64_t todo = __ballot(pending);
+        while (todo) {                                  // uniform: every lane sees the same mask
+          const uint32_t leader = __ffsll((unsigned long long)todo) - 1;
+          const uint32_t v = __shfl(key[u] & 511u, leader, 64);
+          const uint64_t same = __ballot(pending && (key[u] & 511u) == v);
+          if (lane_id() == leader) atomicAdd(&gh[v], (uint32_t)__popcll(same));
+          if ((same >> lane_id()) & 1ull) pending = false;
+          todo &= ~same;
+        }
       }
     }
   }
@@ -235,11 +244,20 @@ __global__ __launch_bounds__(kThreads) void k_topk_count(Tables T) {
     const WorkItem wi = work_item(T, i);
     const uint32_t t = T.sel_prefix[wi.seg], ns = T.stage_n[wi.w];
     uint32_t g = 0, e = 0;
-    for (uint32_t q0 = 0; q0 < ns; q0 += 64) {
-      const uint32_t q = q0 + lane_id();
-      const uint32_t key = q < ns ? T.stage_key[wi.base + q] : 0u;
-      g += __popcll(__ballot(q < ns && key > t));
-      e += __popcll(__ballot(q < ns && key == t));
+    for (uint32_t q0 = 0; q0 < ns; q0 += 64 * kBatch) {
+      uint32_t key[kBatch];
+      bool in[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const uint32_t q = q0 + u * 64 + lane_id();
+        in[u] = q < ns;
+        key[u] = in[u] ? T.stage_key[wi.base + q] : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        g += __popcll(__ballot(in[u] && key[u] > t));
+        e += __popcll(__ballot(in[u] && key[u] == t));
+      }
     }
     if (lane_id() == 0) T.chunk_cnt[wi.w] = make_uint2(g, e);
   }
@@ -284,25 +302,34 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
     const uint32_t first = before.x + (before.y < ties ? before.y : ties);   // the chunk's first slot
     uint32_t run_g = before.x, run_e = before.y;
     uint32_t per_sweep[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // winners per sweep (wave-uniform)
-    for (uint32_t q0 = 0; q0 < ns; q0 += 64) {
-      const uint32_t q = q0 + lane_id();
-      uint32_t key = 0, j = wi.cd.j0;
-      if (q < ns) { key = T.stage_key[wi.base + q]; j = T.stage_idx[wi.base + q]; }
-      const bool isg = q < ns && key > t, ise = q < ns && key == t;
-      const uint64_t mg = __ballot(isg), me = __ballot(ise);
-      const uint32_t g = run_g + lanes_below(mg), eq = run_e + lanes_below(me);
-      const bool win = isg || (ise && eq < ties);
-      if (win) {
-        const uint32_t pos = g + (eq < ties ? eq : ties);
-        T.msg_idx[mbase + pos] = j;
-        T.msg_val[mbase + pos] = T.stage_val[wi.base + q];
-      }
-      const uint32_t sw = (j - wi.cd.j0) / (uint32_t)kSweep;
+    for (uint32_t q0 = 0; q0 < ns; q0 += 64 * kBatch) {
+      uint32_t key[kBatch], j[kBatch];
+      bool in[kBatch];
 #pragma unroll
-      for (uint32_t s2 = 0; s2 < 8; ++s2)
-        if (s2 < T.SW) per_sweep[s2] += __popcll(__ballot(win && sw == s2));
-      run_g += __popcll(mg);
-      run_e += __popcll(me);
+      for (int u = 0; u < kBatch; ++u) {
+        const uint32_t q = q0 + u * 64 + lane_id();
+        in[u] = q < ns;
+        key[u] = in[u] ? T.stage_key[wi.base + q] : 0u;
+        j[u] = in[u] ? T.stage_idx[wi.base + q] : wi.cd.j0;
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {                // groups in index order
+        const bool isg = in[u] && key[u] > t, ise = in[u] && key[u] == t;
+        const uint64_t mg = __ballot(isg), me = __ballot(ise);
+        const uint32_t g = run_g + lanes_below(mg), eq = run_e + lanes_below(me);
+        const bool win = isg || (ise && eq < ties);
+        if (win) {
+          const uint32_t pos = g + (eq < ties ? eq : ties);
+          T.msg_idx[mbase + pos] = j[u];
+          T.msg_val[mbase + pos] = T.stage_val[wi.base + q0 + u * 64 + lane_id()];
+        }
+        const uint32_t sw = (j[u] - wi.cd.j0) / (uint32_t)kSweep;
+#pragma unroll
+        for (uint32_t s2 = 0; s2 < 8; ++s2)
+          if (s2 < T.SW) per_sweep[s2] += __popcll(__ballot(win && sw == s2));
+        run_g += __popcll(mg);
+        run_e += __popcll(me);
+      }
     }
     if (lane_id() == 0) {
       uint32_t at = first;
