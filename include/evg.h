@@ -183,6 +183,18 @@ evg_status evg_message(evg_ctx* c, uint32_t r, uint32_t l, uint32_t* idx, float*
  * out: DEVICE array of evg_padded_numel floats.  Asynchronous on the stream. */
 evg_status evg_average(evg_ctx* c, float* out);
 
+/* Checkpoint / resume.  The five arenas are the caller's to save; everything else a run
+ * depends on (thresholds, last-event iterations, mailbox flags, slope histories, counters,
+ * the norm partial sums and radix histograms carried from the last update pass, the
+ * iteration count) goes into one opaque HOST blob.  evg_state_export waits for the stream.
+ * evg_state_import expects a context created with the same configuration whose arenas
+ * already hold the saved contents; a blob from a different configuration is rejected with
+ * EVG_ERR_INVALID.  After import, evg_step continues exactly (bit for bit) where the
+ * exporting context stopped. */
+uint64_t evg_state_size(evg_ctx* c); /* bytes needed for the blob; 0 if c is NULL */
+evg_status evg_state_export(evg_ctx* c, void* blob, uint64_t capacity);
+evg_status evg_state_import(evg_ctx* c, const void* blob, uint64_t size);
+
 /* Per-phase GPU time.  enable != 0 starts bracketing every phase of every later
  * step with HIP events on the context's stream (and clears earlier samples);
  * evg_timing_read waits for the stream and returns, per phase, the summed

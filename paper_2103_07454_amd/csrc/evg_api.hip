@@ -536,6 +536,98 @@ evg_status evg_average(evg_ctx* c, float* out) {
   return EVG_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+struct StateHeader {
+  char magic[8];
+  uint32_t version, P, L, C, SW, S, hist_len, topk_ppm, trigger_kind, norm_mode, thr_mode, pad;
+  uint64_t Npad, iters;
+  int64_t last_iter;
+};
+
+struct Piece { void* dev; size_t bytes; };
+
+// Every library-owned array a later step reads before writing it.
+std::vector<Piece> state_pieces(evg_ctx* c) {
+  const Tables& t = c->t;
+  const size_t S = t.S, sweeps = (size_t)t.P * t.C * t.SW;
+  std::vector<Piece> v = {
+      {t.delta, S * 4}, {t.last_norm, S * 4}, {t.delta_before, S * 4}, {t.last_event, S * 4},
+      {t.valid_l, S}, {t.valid_r, S}, {t.fired, S}, {t.near_tie, S},
+      {t.ev_full, S * 4}, {t.ev_topk, S * 4}, {t.near_cnt, S * 4}, {t.nonfinite_cnt, S * 4},
+      {t.slope_hist, S * t.hist_len * 4}, {t.slope_cnt, S * 4}, {t.partials, sweeps * 8}};
+  if (t.partials_hat) { v.push_back({t.partials_hat, sweeps * 8}); v.push_back({t.xhat_sq, S * 8}); }
+  if (t.hist) v.push_back({t.hist, S * kHistBins * 4});
+  return v;
+}
+
+StateHeader state_header(evg_ctx* c) {
+  StateHeader h{};
+  std::memcpy(h.magic, "EVGSTATE", 8);
+  h.version = 1;
+  h.P = c->t.P; h.L = c->t.L; h.C = c->t.C; h.SW = c->t.SW; h.S = c->t.S;
+  h.hist_len = c->t.hist_len;
+  h.topk_ppm = c->cfg.topk_ppm;
+  h.trigger_kind = c->cfg.trigger_kind;
+  h.norm_mode = c->cfg.norm_mode;
+  h.thr_mode = c->cfg.thr_mode;
+  h.Npad = c->t.Npad;
+  h.iters = c->iters;
+  h.last_iter = c->last_iter;
+  return h;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t evg_state_size(evg_ctx* c) {
+  if (!c) return 0;
+  uint64_t n = sizeof(StateHeader);
+  for (const Piece& p : state_pieces(c)) n += p.bytes;
+  return n;
+}
+
+evg_status evg_state_export(evg_ctx* c, void* blob, uint64_t capacity) {
+  if (!c || !blob) return fail(EVG_ERR_INVALID, "context and blob must be non-NULL");
+  if (capacity < evg_state_size(c))
+    return fail(EVG_ERR_INVALID, "blob holds %llu bytes, %llu needed", (unsigned long long)capacity,
+                (unsigned long long)evg_state_size(c));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  const StateHeader h = state_header(c);
+  char* out = static_cast<char*>(blob);
+  std::memcpy(out, &h, sizeof h);
+  out += sizeof h;
+  for (const Piece& p : state_pieces(c)) {
+    HIP_TRY(hipMemcpy(out, p.dev, p.bytes, hipMemcpyDeviceToHost));
+    out += p.bytes;
+  }
+  return EVG_OK;
+}
+
+evg_status evg_state_import(evg_ctx* c, const void* blob, uint64_t size) {
+  if (!c || !blob) return fail(EVG_ERR_INVALID, "context and blob must be non-NULL");
+  if (size != evg_state_size(c)) return fail(EVG_ERR_INVALID, "blob size does not match this configuration");
+  StateHeader got;
+  std::memcpy(&got, blob, sizeof got);
+  StateHeader want = state_header(c);
+  want.iters = got.iters;
+  want.last_iter = got.last_iter;
+  if (std::memcmp(&got, &want, sizeof got) != 0)
+    return fail(EVG_ERR_INVALID, "blob was exported from a different configuration or version");
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  const char* in = static_cast<const char*>(blob) + sizeof got;
+  for (const Piece& p : state_pieces(c)) {
+    HIP_TRY(hipMemcpy(p.dev, in, p.bytes, hipMemcpyHostToDevice));
+    in += p.bytes;
+  }
+  c->iters = got.iters;
+  c->last_iter = got.last_iter;
+  return EVG_OK;
+}
+
 evg_status evg_timing(evg_ctx* c, int enable) {
   if (!c) return fail(EVG_ERR_INVALID, "context is NULL");
   evg_status st = c->drain_timers();

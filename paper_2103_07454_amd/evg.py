@@ -25,7 +25,8 @@ TRIGGER_DRIFT_NORM, TRIGGER_NORM_DIFF = 0, 1
 PHASES = ("norm", "trigger", "send_full", "topk_select", "topk_send", "update")
 
 EXPORTS = ("evg_padded_numel", "evg_layer_offsets", "evg_init", "evg_step", "evg_stats",
-           "evg_last_decisions", "evg_message", "evg_average", "evg_timing", "evg_timing_read",
+           "evg_last_decisions", "evg_message", "evg_average", "evg_state_size", "evg_state_export",
+           "evg_state_import", "evg_timing", "evg_timing_read",
            "evg_destroy", "evg_strerror", "evg_error_text")
 
 
@@ -88,6 +89,10 @@ def lib():
         l.evg_last_decisions.argtypes = [vp, vp, vp, vp, vp]
         l.evg_message.argtypes = [vp, C.c_uint32, C.c_uint32, vp, vp, C.c_uint64, u64p]
         l.evg_average.argtypes = [vp, vp]
+        l.evg_state_size.restype = C.c_uint64
+        l.evg_state_size.argtypes = [vp]
+        l.evg_state_export.argtypes = [vp, vp, C.c_uint64]
+        l.evg_state_import.argtypes = [vp, vp, C.c_uint64]
         l.evg_timing.argtypes = [vp, C.c_int]
         l.evg_timing_read.argtypes = [vp, C.POINTER(C.c_double), u64p]
         l.evg_destroy.argtypes = [vp]
@@ -272,6 +277,25 @@ class Ring:
         _check(lib().evg_average(self._h, C.c_void_p(out.data_ptr())))
         self.torch.cuda.synchronize(self.device)
         return out.cpu().numpy()[self.layout.index]
+
+    def export_state(self) -> dict:
+        """Checkpoint: host copies of the five arenas (arena layout) plus the library's blob."""
+        n = int(lib().evg_state_size(self._h))
+        blob = np.zeros(n, np.uint8)
+        _check(lib().evg_state_export(self._h, blob.ctypes.data, n))
+        ck = {"blob": blob}
+        for name in ("x", "xhat", "mbox_l", "mbox_r", "vel"):
+            ck[name] = getattr(self, name).cpu().numpy()
+        return ck
+
+    def import_state(self, ck: dict):
+        """Resume from export_state() of a ring with the same configuration."""
+        self.torch.cuda.synchronize(self.device)
+        for name in ("x", "xhat", "mbox_l", "mbox_r", "vel"):
+            getattr(self, name).copy_(self.torch.from_numpy(ck[name]))
+        self.torch.cuda.synchronize(self.device)
+        blob = np.ascontiguousarray(ck["blob"], dtype=np.uint8)
+        _check(lib().evg_state_import(self._h, blob.ctypes.data, blob.size))
 
     def timing(self, enable=True):
         _check(lib().evg_timing(self._h, 1 if enable else 0))

@@ -200,6 +200,37 @@ def test_determinism_across_runs_and_chunkings(evg):
     assert np.array_equal(runs[0][0], runs[2][0])                            # decisions survive re-chunking
 
 
+@pytest.mark.parametrize("mode", ["topk", "whole_hist3", "norm_diff"])
+def test_checkpoint_resume_is_exact(evg, mode):
+    """run(2m) == run(m) + export + import into a fresh context + run(m), bit for bit."""
+    kw = dict(topk=dict(topk_ppm=100_000), whole_hist3=dict(hist_len=3), norm_diff=dict(trigger_kind=1))[mode]
+    w = ragged()
+    a = evg.Ring.from_workload(w, **kw)
+    b = evg.Ring.from_workload(w, **kw)
+    for k in range(12):
+        a.step(k)
+        b.step(k)
+    ck = b.export_state()
+    b.close()
+    c = evg.Ring.from_workload(w, **kw)
+    with pytest.raises(evg.EvgError):
+        evg.Ring.from_workload(w).import_state(ck) if mode != "whole_hist3" else \
+            evg.Ring.from_workload(w, topk_ppm=5).import_state(ck)      # other configuration: refused
+    c.import_state(ck)
+    for k in range(12, 24):
+        a.step(k)
+        c.step(k)
+        da, dc = a.decisions(), c.decisions()
+        assert np.array_equal(da["fired"], dc["fired"]) and np.array_equal(da["norm"], dc["norm"])
+    for name in ("x", "xhat", "vel", "mbox_l", "mbox_r"):
+        assert np.array_equal(a.state(name), c.state(name))
+    sa, sc = a.stats(arrays=True), c.stats(arrays=True)
+    for key in sa:
+        assert np.array_equal(sa[key], sc[key]), key
+    with pytest.raises(evg.EvgError):
+        c.step(5)                                  # the iteration counter came along
+
+
 def test_final_average(evg, oracle_mod):
     w = ragged()
     ring, orc = pair(evg, oracle_mod, w)
