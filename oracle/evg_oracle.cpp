@@ -36,6 +36,9 @@
 //       event is sent whole (a sparse patch has no base to patch).
 //   R7  momentum SGD in heavy-ball form v <- mu v + g, x <- x - lr v (the paper
 //       uses plain SGD, i.e. mu = 0).
+//   R9  delivery_delay = 1 is a deterministic stand-in for the asynchrony of one-sided
+//       puts (Section 7 blames it for threshold oscillations): what is sent in iteration
+//       k is written into the neighbours' memory only after iteration k's updates.
 //   R8  gradients are synthetic: a counter-based Philox4x32-10 stream turned
 //       into normals by Box-Muller with fixed polynomial log/sin/cos.
 //
@@ -76,6 +79,8 @@ struct orc_config {
   uint32_t fan_in_scaling;
   double sigma0, decay;
   float spike_prob, spike_gain;
+  uint32_t delivery_delay;       // 0: a message is visible to the same iteration's updates;
+                                 // 1: it arrives after them (visible from the next iteration)
 };
 
 }  // extern "C"
@@ -181,6 +186,8 @@ struct Oracle {
   std::vector<uint8_t> valid_l, valid_r, fired, near_tie;
   std::vector<uint64_t> ev_full, ev_topk;
   std::vector<std::vector<float>> slope_hist;   // last hist_len slopes per (r,l)
+  struct Flight { uint64_t s; bool whole; std::vector<uint32_t> idx; std::vector<float> val; };
+  std::vector<Flight> in_flight;                // messages sent but not yet delivered (delay 1)
   std::vector<std::vector<uint32_t>> msg_idx;   // last Top-K message per (r,l)
   std::vector<std::vector<float>> msg_val;
   uint64_t near_ties = 0, nonfinite = 0, iters = 0;
@@ -270,7 +277,7 @@ void orc_topk_select(const uint32_t* keys, uint64_t n, uint64_t K, uint32_t* out
 
 void* orc_create(const orc_config* cfg, const float* x0) {
   if (!cfg || !x0 || cfg->P < 3 || cfg->L < 1 || !cfg->layer_numel) return nullptr;
-  if (cfg->hist_len < 1) return nullptr;
+  if (cfg->hist_len < 1 || cfg->delivery_delay > 1) return nullptr;
   Oracle* o = new Oracle();
   o->cfg = *cfg;
   o->numel.assign(cfg->layer_numel, cfg->layer_numel + cfg->L);
@@ -372,8 +379,13 @@ int orc_step(void* h, uint64_t k, const float* grad_or_null, const int8_t* overr
       o.last_event[s] = (int32_t)k;
       float* toR = &o.mbox_r[left * N + o.off[l]];    // I am my left neighbour's right
       float* toL = &o.mbox_l[right * N + o.off[l]];   // and my right neighbour's left
+      const bool now = c.delivery_delay == 0;
       if (c.topk_ppm == 0 || first) {
-        for (uint64_t j = 0; j < n; ++j) { hs[j] = xs[j]; toR[j] = xs[j]; toL[j] = xs[j]; }
+        if (!now) o.in_flight.push_back({s, true, {}, std::vector<float>(xs, xs + n)});
+        for (uint64_t j = 0; j < n; ++j) {
+          hs[j] = xs[j];
+          if (now) { toR[j] = xs[j]; toL[j] = xs[j]; }
+        }
         o.fired[s] = 1; o.ev_full[s]++;
       } else {
         const uint64_t K = o.topk_count(n);
@@ -383,12 +395,16 @@ int orc_step(void* h, uint64_t k, const float* grad_or_null, const int8_t* overr
         topk_select(keys.data(), n, K, o.msg_idx[s]);
         for (uint32_t j : o.msg_idx[s]) {
           o.msg_val[s].push_back(xs[j]);
-          hs[j] = xs[j]; toR[j] = xs[j]; toL[j] = xs[j];
+          hs[j] = xs[j];
+          if (now) { toR[j] = xs[j]; toL[j] = xs[j]; }
         }
+        if (!now) o.in_flight.push_back({s, false, o.msg_idx[s], o.msg_val[s]});
         o.fired[s] = 2; o.ev_topk[s]++;
       }
-      o.valid_r[(uint64_t)left * L + l] = 1;
-      o.valid_l[(uint64_t)right * L + l] = 1;
+      if (now) {
+        o.valid_r[(uint64_t)left * L + l] = 1;
+        o.valid_l[(uint64_t)right * L + l] = 1;
+      }
     }
   }
 
@@ -417,6 +433,21 @@ int orc_step(void* h, uint64_t k, const float* grad_or_null, const int8_t* overr
       }
     }
   }
+  // ---- delayed delivery: the puts of this iteration land now ----
+  for (const Oracle::Flight& f : o.in_flight) {
+    const uint32_t r = (uint32_t)(f.s / L), l = (uint32_t)(f.s % L);
+    const uint32_t left = (r + P - 1) % P, right = (r + 1) % P;
+    float* toR = &o.mbox_r[left * N + o.off[l]];
+    float* toL = &o.mbox_l[right * N + o.off[l]];
+    if (f.whole) {
+      for (uint64_t j = 0; j < f.val.size(); ++j) { toR[j] = f.val[j]; toL[j] = f.val[j]; }
+    } else {
+      for (uint64_t q = 0; q < f.idx.size(); ++q) { toR[f.idx[q]] = f.val[q]; toL[f.idx[q]] = f.val[q]; }
+    }
+    o.valid_r[(uint64_t)left * L + l] = 1;
+    o.valid_l[(uint64_t)right * L + l] = 1;
+  }
+  o.in_flight.clear();
   o.last_iter = (int64_t)k;
   o.iters++;
   return 0;

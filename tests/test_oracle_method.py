@@ -498,3 +498,52 @@ def test_norm_difference_trigger_adaptive_and_topk_invariants(oracle_mod):
                     assert d["norm"][r, l] < d["delta_before"][r, l]
     t = o.totals()
     assert w.P * w.L * 2 <= t["events_total"] < w.P * w.L * 25
+
+
+# --------------------------------------------------------------------------
+# delayed delivery: what is sent in iteration k is averaged in from iteration k + 1
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("P", [3, 5])
+def test_delayed_delivery_is_dpsgd_with_one_step_old_neighbours(oracle_mod, P):
+    numel = [6, 17]
+    n = sum(numel)
+    lr, mu = 0.05, 0.9
+    o, x0 = make(oracle_mod, numel, P, thr_mode=0, thr_fixed=0.0, lr=lr, momentum=mu, grad_mode=1,
+                 delivery_delay=1)
+    W = ring_matrix(P)
+    Wn = W - np.eye(P) / 3.0               # the neighbours' part of the mixing matrix
+    X = x0.astype(np.float64).T
+    X_old = None
+    V = np.zeros_like(X)
+    for k in range(20):
+        g = inputs.random_grads(P, n, 300 + k, 0.1)
+        o.step(k, grad=g)
+        V = mu * V + g.astype(np.float64).T
+        if X_old is None:
+            X_new = X - lr * V             # nothing has arrived yet: a plain local step
+        else:
+            X_new = X / 3.0 + X_old @ Wn - lr * V
+        X_old, X = X, X_new
+        np.testing.assert_allclose(o.state("x").T, X, rtol=0, atol=2e-6 * np.abs(X).max())
+    tb = o.tables()
+    assert tb["valid_l"].all() and tb["valid_r"].all()
+
+
+def test_delayed_delivery_topk_keeps_the_ring_invariant(oracle_mod):
+    w = small_workload(topk_ppm=200_000)
+    o = oracle_mod.Oracle.from_workload(w, delivery_delay=1)
+    numel = w.layer_numel.astype(np.int64)
+    off = np.concatenate([[0], np.cumsum(numel)])
+    for k in range(20):
+        o.step(k)
+        xhat, ml, mr, tb = o.state("xhat"), o.state("mbox_l"), o.state("mbox_r"), o.tables()
+        for r in range(w.P):
+            for l in range(w.L):
+                sl = slice(off[l], off[l + 1])
+                if tb["last_event_iter"][r, l] >= 0:      # delivered by the end of the iteration
+                    assert np.array_equal(ml[(r + 1) % w.P, sl], xhat[r, sl])
+                    assert np.array_equal(mr[(r - 1) % w.P, sl], xhat[r, sl])
+    a = oracle_mod.Oracle.from_workload(w)
+    for k in range(20):
+        a.step(k)
+    assert not np.array_equal(a.state("x"), o.state("x"))     # the delay does change the run
