@@ -93,6 +93,10 @@ typedef struct {
                                    Section 4); EVG_TRIGGER_NORM_DIFF: test | ||x|| - ||xhat|| |
                                    (the wording of Section 4: "when the norm has changed by
                                    some threshold"); Eq. 3 then uses the same quantity      */
+  uint32_t delivery_delay;      /* 0: a message is visible to the updates of the iteration it is
+                                   sent in; 1: it lands after them and is used from the next
+                                   iteration on (a deterministic stand-in for the asynchrony of
+                                   one-sided puts, Section 7)                                 */
   evg_synth synth;
   /* DEVICE arenas owned by the caller, each P * evg_padded_numel() floats,
    * 16-byte aligned, non-overlapping, alive until evg_destroy.  Worker r's
@@ -139,7 +143,8 @@ enum {
   EVG_PH_TOPK_SELECT = 3,/* threshold-key search for the Top-K set                   */
   EVG_PH_TOPK_SEND = 4,  /* pack (index, value) messages, put them                   */
   EVG_PH_UPDATE = 5,     /* fused averaging + momentum SGD (+ next drift norms)      */
-  EVG_PH_COUNT = 6
+  EVG_PH_DELIVER = 6,    /* delivery_delay = 1 only: the iteration's puts land       */
+  EVG_PH_COUNT = 7
 };
 
 /* Size in floats of one worker's slice of an arena: every tensor start is

@@ -204,6 +204,7 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   if (cfg->grad_mode > EVG_GRAD_BUFFER) return fail(EVG_ERR_INVALID, "unknown grad_mode %u", cfg->grad_mode);
   if (cfg->norm_mode > EVG_NORM_SEPARATE) return fail(EVG_ERR_INVALID, "unknown norm_mode %u", cfg->norm_mode);
   if (cfg->trigger_kind > EVG_TRIGGER_NORM_DIFF) return fail(EVG_ERR_INVALID, "unknown trigger_kind %u", cfg->trigger_kind);
+  if (cfg->delivery_delay > 1) return fail(EVG_ERR_INVALID, "delivery_delay must be 0 or 1");
   const uint32_t ce = cfg->chunk_elems ? cfg->chunk_elems : 8192u;
   if (ce != 1024 && ce != 2048 && ce != 4096 && ce != 8192)
     return fail(EVG_ERR_INVALID, "chunk_elems must be 0, 1024, 2048, 4096 or 8192");
@@ -399,6 +400,7 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   a.force_first = g.force_first ? 1u : 0u;
   a.topk_on = g.topk_ppm ? 1u : 0u;
   a.topk_key = g.topk_key;
+  a.delay = g.delivery_delay;
   a.hist_fused = (g.topk_ppm && g.norm_mode == EVG_NORM_FUSED) ? 1u : 0u;
   const bool norm_diff = g.trigger_kind == EVG_TRIGGER_NORM_DIFF;
   // fused + whole-tensor sends: xhat's norm is a scalar per tensor and xhat is never read
@@ -430,7 +432,7 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   }
   {
     Phase ph(c, EVG_PH_SEND_FULL);
-    HIP_TRY(launch_copy(t, c->chunk_elems, c->work_grid, c->stream));
+    HIP_TRY(launch_copy(t, c->chunk_elems, c->work_grid, !a.delay, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
   }
   if (a.topk_on) {
@@ -449,6 +451,11 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
     Phase ph(c, EVG_PH_UPDATE);
     const int norm = !fused ? 0 : !norm_diff ? 1 : g.topk_ppm ? 3 : 2;
     HIP_TRY(launch_update(t, a, g.synth.dist, g.grad_mode, norm, c->stream));
+    if ((st = ph.end()) != EVG_OK) return st;
+  }
+  if (a.delay) {
+    Phase ph(c, EVG_PH_DELIVER);
+    HIP_TRY(launch_deliver(t, c->chunk_elems, c->work_grid, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
   }
   c->last_iter = (int64_t)iter;
@@ -573,6 +580,7 @@ StateHeader state_header(evg_ctx* c) {
   h.trigger_kind = c->cfg.trigger_kind;
   h.norm_mode = c->cfg.norm_mode;
   h.thr_mode = c->cfg.thr_mode;
+  h.pad = c->cfg.delivery_delay;
   h.Npad = c->t.Npad;
   h.iters = c->iters;
   h.last_iter = c->last_iter;

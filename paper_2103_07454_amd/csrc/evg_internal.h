@@ -76,6 +76,7 @@ struct StepArgs {
   uint32_t norm_src;       // what k_trigger finds: 0 squared drift in partials; 1 squared x in
                            // partials, squared xhat in xhat_sq once a tensor has sent; 2 squared x
                            // and squared xhat in partials / partials_hat
+  uint32_t delay;          // messages of this iteration land after its updates
   uint32_t hist_fused;     // the update pass of the previous iteration already built pass A's histograms
   uint32_t key0, key1;
   double decay_pow;        // decay^k
@@ -91,7 +92,8 @@ hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t dist, uint
 hipError_t launch_trigger(const Tables& t, const StepArgs& a, hipStream_t s);
 hipError_t launch_scan(const Tables& t, hipStream_t s);
 hipError_t launch_expand(const Tables& t, hipStream_t s);
-hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s);
+hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, bool mailboxes, hipStream_t s);
+hipError_t launch_deliver(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s);
 hipError_t launch_topk_select(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid,
                               hipStream_t s);
 hipError_t launch_topk_send(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid,

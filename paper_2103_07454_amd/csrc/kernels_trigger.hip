@@ -75,8 +75,10 @@ __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
     if (!A.topk_on || khat < 0) { code = 1; T.ev_full[seg] += 1; }
     else { code = 2; T.ev_topk[seg] += 1; }
     const uint32_t left = (r + T.P - 1) % T.P, right = (r + 1) % T.P;
-    T.valid_r[left * T.L + l] = 1;    // I am my left neighbour's right-hand source
-    T.valid_l[right * T.L + l] = 1;
+    if (!A.delay) {                     // otherwise set when the put lands (k_deliver)
+      T.valid_r[left * T.L + l] = 1;    // I am my left neighbour's right-hand source
+      T.valid_l[right * T.L + l] = 1;
+    }
   }
   T.fired[seg] = code;
 }
@@ -119,7 +121,8 @@ __global__ __launch_bounds__(kThreads) void k_expand(Tables T) {
   for (uint32_t i = lane_id(); i < ld.nchunks; i += 64) dst[i] = first + i;
 }
 
-template <int SWEEPS>
+// MAILBOXES = false: only xhat takes the sent values now; the puts land later (k_deliver).
+template <int SWEEPS, bool MAILBOXES>
 __global__ __launch_bounds__(kThreads) void k_copy(Tables T) {
   const uint32_t n = T.counts[0];
   for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
@@ -137,8 +140,10 @@ __global__ __launch_bounds__(kThreads) void k_copy(Tables T) {
       if (e < cd.len) {
         const float4 v = ld4s(src + e);
         st4s(d0 + e, v);
-        st4s(d1 + e, v);
-        st4s(d2 + e, v);
+        if (MAILBOXES) {
+          st4s(d1 + e, v);
+          st4s(d2 + e, v);
+        }
       }
     }
   }
@@ -161,12 +166,56 @@ hipError_t launch_expand(const Tables& t, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s) {
+// Delayed delivery: after the updates, every tensor that sent in this iteration (whole
+// or Top-K) lands in its neighbours' mailboxes.  What a neighbour must hold afterwards is
+// exactly the sender's xhat (entries that were not sent are equal already), so each listed
+// chunk of xhat is copied, and the receivers' slots are marked as filled.
+template <int SWEEPS>
+__global__ __launch_bounds__(kThreads) void k_deliver(Tables T) {
+  const uint32_t n_full = T.counts[0], n = n_full + T.counts[1];
+  for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
+    const uint32_t w = i < n_full ? T.work_full[i] : T.work_topk[i - n_full];
+    const uint32_t r = w / T.C, c = w % T.C;
+    const ChunkDesc cd = T.chunks[c];
+    const uint32_t left = (r + T.P - 1) % T.P, right = (r + 1) % T.P;
+    const float* src = T.xhat + (size_t)r * T.Npad + cd.off;
+    float* d1 = T.mbox_r + (size_t)left * T.Npad + cd.off;
+    float* d2 = T.mbox_l + (size_t)right * T.Npad + cd.off;
+#pragma unroll
+    for (int it = 0; it < SWEEPS; ++it) {
+      const uint32_t e = it * kSweep + threadIdx.x * kLaneElems;
+      if (e < cd.len) {
+        const float4 v = ld4s(src + e);
+        st4s(d1 + e, v);
+        st4s(d2 + e, v);
+      }
+    }
+    if (threadIdx.x == 0 && cd.j0 == 0) {     // the tensor's first chunk speaks for the tensor
+      T.valid_r[left * T.L + cd.layer] = 1;
+      T.valid_l[right * T.L + cd.layer] = 1;
+    }
+  }
+}
+
+hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, bool mailboxes, hipStream_t s) {
+  const dim3 g(grid), b(kThreads);
   switch (chunk_elems / kSweep) {
-    case 1: k_copy<1><<<dim3(grid), dim3(kThreads), 0, s>>>(t); break;
-    case 2: k_copy<2><<<dim3(grid), dim3(kThreads), 0, s>>>(t); break;
-    case 4: k_copy<4><<<dim3(grid), dim3(kThreads), 0, s>>>(t); break;
-    case 8: k_copy<8><<<dim3(grid), dim3(kThreads), 0, s>>>(t); break;
+    case 1: if (mailboxes) k_copy<1, true><<<g, b, 0, s>>>(t); else k_copy<1, false><<<g, b, 0, s>>>(t); break;
+    case 2: if (mailboxes) k_copy<2, true><<<g, b, 0, s>>>(t); else k_copy<2, false><<<g, b, 0, s>>>(t); break;
+    case 4: if (mailboxes) k_copy<4, true><<<g, b, 0, s>>>(t); else k_copy<4, false><<<g, b, 0, s>>>(t); break;
+    case 8: if (mailboxes) k_copy<8, true><<<g, b, 0, s>>>(t); else k_copy<8, false><<<g, b, 0, s>>>(t); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_deliver(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s) {
+  const dim3 g(grid), b(kThreads);
+  switch (chunk_elems / kSweep) {
+    case 1: k_deliver<1><<<g, b, 0, s>>>(t); break;
+    case 2: k_deliver<2><<<g, b, 0, s>>>(t); break;
+    case 4: k_deliver<4><<<g, b, 0, s>>>(t); break;
+    case 8: k_deliver<8><<<g, b, 0, s>>>(t); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

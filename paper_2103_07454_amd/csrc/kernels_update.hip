@@ -151,8 +151,9 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
       const uint32_t left = (r + T.P - 1) % T.P, right = (r + 1) % T.P;
       const uint32_t moff = T.layers[cd.layer].msg_off, j_lo = cd.j0 + sub * kSweep;
       const Slice s0 = message_slice(T, r, cd.layer, c, sub, moff);
-      const Slice s1 = message_slice(T, left, cd.layer, c, sub, moff);
-      const Slice s2 = message_slice(T, right, cd.layer, c, sub, moff);
+      Slice s1 = message_slice(T, left, cd.layer, c, sub, moff);
+      Slice s2 = message_slice(T, right, cd.layer, c, sub, moff);
+      if (A.delay) { s1.n = 0; s2.n = 0; }   // the neighbours' messages land after this pass
       if (s0.n | s1.n | s2.n) {          // uniform
         if (threadIdx.x < 96) pm[threadIdx.x] = 0;
         __syncthreads();

@@ -174,6 +174,21 @@ def test_norm_difference_trigger(evg, oracle_mod, mode):
     assert rep["rel"]["x"] <= 1e-5
 
 
+@pytest.mark.parametrize("mode", ["whole", "topk", "topk_separate_norm", "fixed"])
+def test_delayed_delivery(evg, oracle_mod, mode):
+    """Messages land after the iteration's updates (delivery_delay = 1)."""
+    from helpers import lockstep
+    kw = dict(whole={}, topk=dict(topk_ppm=100_000), topk_separate_norm=dict(topk_ppm=100_000),
+              fixed=dict(thr_mode=inputs.THR_FIXED, thr_fixed=5e-2))[mode]
+    w = ragged(**kw)
+    gpu = dict(norm_mode=evg.NORM_SEPARATE) if "separate" in mode else {}
+    ring, orc = pair(evg, oracle_mod, w, gpu=gpu, delivery_delay=1)
+    rep = lockstep(ring, orc, w.iters, sample_messages=32)
+    note(f"delayed/{mode}", rep)
+    assert all(rep["bitwise"].values())
+    assert 0 < ring.stats()["events_total"] < ring.stats()["regular_events"]
+
+
 def test_separate_norm_pass_matches_fused(evg):
     w = ragged(topk_ppm=100_000)
     a = evg.Ring.from_workload(w)
