@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--trigger-kind", type=int, default=0,
                     help="0 = norm of the drift (default, the benchmark configurations); "
                          "1 = difference of the norms")
+    ap.add_argument("--delivery-delay", type=int, default=0,
+                    help="1 = messages land after the iteration's updates (not a benchmark configuration)")
     ap.add_argument("--diag-grad-buffer", action="store_true",
                     help="diagnostic only (not the named workload): gradients from a fixed device buffer")
     args = ap.parse_args()
@@ -85,8 +87,9 @@ def main():
     def make():
         if args.diag_grad_buffer:
             return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk, grad_mode=evg.GRAD_BUFFER,
-                                          trigger_kind=args.trigger_kind)
-        return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk, trigger_kind=args.trigger_kind)
+                                          trigger_kind=args.trigger_kind, delivery_delay=args.delivery_delay)
+        return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk, trigger_kind=args.trigger_kind,
+                                      delivery_delay=args.delivery_delay)
 
     ring = make()
     if args.diag_grad_buffer:
@@ -125,7 +128,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name + ("+DIAG_GRAD_BUFFER" if args.diag_grad_buffer else "")
-                   + ("+NORM_DIFF_TRIGGER" if args.trigger_kind else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
+                   + ("+NORM_DIFF_TRIGGER" if args.trigger_kind else "")
+                   + ("+DELAYED_DELIVERY" if args.delivery_delay else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
                    "threshold": "adaptive" if w.thr_mode else "fixed", "topk_ppm": w.topk_ppm,
                    "chunk_elems": args.chunk or 8192,
                    "fraction_fired_full": f_full, "fraction_fired_topk": f_topk,
@@ -150,6 +154,17 @@ def main():
                            "avg_launch_ms": avg_ms, "launches": n_upd,
                            "algorithmic_bytes_per_launch": upd_bytes}
         out["phase_ms_per_step"] = {p: ms / max(1, args.steps) for p, (ms, n) in phases.items()}
+    # the final model average (last line of Algorithm B): one pass over x of all workers
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ring.average()
+    ev0.record(ring.stream)
+    avg_reps = 5
+    for _ in range(avg_reps):
+        evg._check(evg.lib().evg_average(ring._h, ring.xhat.data_ptr()))   # xhat is scratch now
+    ev1.record(ring.stream)
+    torch.cuda.synchronize()
+    avg_ms = ev0.elapsed_time(ev1) / avg_reps
+    out["final_average"] = {"ms": avg_ms, "achieved_GBps": 4.0 * elems / (avg_ms * 1e-3) / 1e9}
     ring.close()
     del ring
     torch.cuda.empty_cache()
