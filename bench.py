@@ -40,7 +40,7 @@ def cpu_baseline(inputs, w, seconds_hint=20.0):
     """The oracle as it stands, single thread, on a bounded sample of the same
     workload: fewer ring workers, first iterations."""
     import oracle
-    P, iters = 4, 5
+    P, iters = 8, 5
     ws = w.scaled(P=P)
     x0 = inputs.replicate(ws.x0(), P)
     orc = oracle.Oracle.from_workload(ws, x0)

@@ -14,7 +14,10 @@
  *
  * Conventions for every call
  *   - returns an evg_status; never throws or aborts across the ABI; on failure
- *     output arguments are left untouched and evg_error_text() explains.
+ *     evg_error_text() explains, handles and counters are left untouched (array
+ *     outputs of a failed evg_stats / evg_last_decisions may be partly written).
+ *   - the HIP device that holds the arenas must be the current device of the
+ *     calling thread for every call.
  *   - pointers are HOST pointers unless the comment says DEVICE.
  *   - a context is bound to one HIP stream and is not re-entrant: calls on one
  *     context must not overlap.  evg_step only enqueues work (no host sync).

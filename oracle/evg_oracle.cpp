@@ -181,7 +181,7 @@ struct Oracle {
   // per worker state, [P][N]
   std::vector<float> x, xhat, mbox_l, mbox_r, vel;
   // per (worker, tensor), [P*L]
-  std::vector<float> delta, last_norm, delta_before, prev_event_norm;
+  std::vector<float> delta, last_norm, delta_before;
   std::vector<int32_t> last_event;
   std::vector<uint8_t> valid_l, valid_r, fired, near_tie;
   std::vector<uint64_t> ev_full, ev_topk;
@@ -297,7 +297,6 @@ void* orc_create(const orc_config* cfg, const float* x0) {
   o->delta.assign(PL, cfg->thr_mode == 0 ? cfg->thr_fixed : cfg->delta_init);
   o->last_norm.assign(PL, 0.0f);
   o->delta_before.assign(PL, 0.0f);
-  o->prev_event_norm.assign(PL, 0.0f);
   o->last_event.assign(PL, -1);
   o->valid_l.assign(PL, 0); o->valid_r.assign(PL, 0);
   o->fired.assign(PL, 0); o->near_tie.assign(PL, 0);

@@ -359,7 +359,6 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
     TRY_OR_FREE(c->dalloc(&t.stage_val, (uint64_t)P * Npad, false));
     TRY_OR_FREE(c->dalloc(&t.chunk_cnt, P * C, true));
     TRY_OR_FREE(c->dalloc(&t.chunk_before, P * C, true));
-    TRY_OR_FREE(c->dalloc(&t.chunk_out, P * C, true));
     TRY_OR_FREE(c->dalloc(&t.chunk_sub, P * C * (t.SW + 1), true));
     TRY_OR_FREE(c->dalloc(&t.msg_idx, (uint64_t)P * ktot, true));
     TRY_OR_FREE(c->dalloc(&t.msg_val, (uint64_t)P * ktot, true));

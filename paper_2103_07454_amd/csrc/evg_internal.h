@@ -54,7 +54,6 @@ struct Tables {
                            // start at the chunk's arena offset, in ascending index order
   uint2* chunk_cnt;        // [P*C] (keys above threshold, keys equal) per chunk
   uint2* chunk_before;     // [P*C] the same, summed over the tensor's earlier chunks
-  uint2* chunk_out;        // [P*C] (first message slot, winners) per chunk
   uint32_t* chunk_sub;     // [P*C*(SW+1)] winners before each 1024-element sweep of a chunk,
                            // as message slots (entry 0 = the chunk's first slot)
   uint32_t* msg_idx; float* msg_val;          // [P*Ktot]

@@ -269,7 +269,6 @@ __global__ __launch_bounds__(64) void k_topk_chunkscan(Tables T) {
   if (T.fired[seg] != 2) return;
   const uint32_t r = seg / T.L;
   const LayerDesc ld = T.layers[seg % T.L];
-  const uint32_t ties = T.sel_krem[seg];
   const uint32_t first = r * T.C + ld.chunk0;
   uint32_t carry_g = 0, carry_e = 0;
   for (uint32_t b = 0; b < ld.nchunks; b += 64) {
@@ -278,11 +277,7 @@ __global__ __launch_bounds__(64) void k_topk_chunkscan(Tables T) {
     if (i < ld.nchunks) ce = T.chunk_cnt[first + i];
     const uint32_t ig = wave_incl_scan(ce.x), ie = wave_incl_scan(ce.y);
     const uint32_t gb = carry_g + ig - ce.x, eb = carry_e + ie - ce.y;
-    if (i < ld.nchunks) {
-      const uint32_t take_e = eb >= ties ? 0u : (ties - eb < ce.y ? ties - eb : ce.y);
-      T.chunk_before[first + i] = make_uint2(gb, eb);
-      T.chunk_out[first + i] = make_uint2(gb + (eb < ties ? eb : ties), ce.x + take_e);
-    }
+    if (i < ld.nchunks) T.chunk_before[first + i] = make_uint2(gb, eb);
     carry_g += __shfl(ig, 63, 64);
     carry_e += __shfl(ie, 63, 64);
   }
