@@ -182,7 +182,8 @@ evg_status evg_last_decisions(evg_ctx* c, uint8_t* fired, uint8_t* near_tie, flo
 
 /* The Top-K message worker r sent for tensor l in the most recent step: ascending
  * element indices within the tensor and their values (Section 7: values + indices
- * = 2K words).  *count = K, or 0 if (r, l) sent no Top-K message; at most cap
+ * = 2K words).  *count = K, or 0 if (r, l) sent no Top-K message (or no step has run
+ * in this context since evg_init / evg_state_import); at most cap
  * entries are copied to the HOST arrays idx / val (either may be NULL). */
 evg_status evg_message(evg_ctx* c, uint32_t r, uint32_t l, uint32_t* idx, float* val,
                        uint64_t cap, uint64_t* count);

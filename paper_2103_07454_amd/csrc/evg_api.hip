@@ -56,6 +56,7 @@ struct evg_ctx {
   uint64_t N = 0;                   // unpadded elements per worker
   uint64_t iters = 0;
   int64_t last_iter = -1;
+  bool messages_live = false;       // the message buffers hold the last step's messages
   // timing
   bool timing = false;
   std::vector<TimerPair> pending;
@@ -459,6 +460,7 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   }
   c->last_iter = (int64_t)iter;
   c->iters += 1;
+  c->messages_live = true;
   return EVG_OK;
 }
 
@@ -523,7 +525,7 @@ evg_status evg_message(evg_ctx* c, uint32_t r, uint32_t l, uint32_t* idx, float*
   HIP_TRY(hipStreamSynchronize(c->stream));
   uint8_t code = 0;
   HIP_TRY(hipMemcpy(&code, t.fired + (size_t)r * t.L + l, 1, hipMemcpyDeviceToHost));
-  if (code != 2 || !c->cfg.topk_ppm) {
+  if (code != 2 || !c->cfg.topk_ppm || !c->messages_live) {
     *count = 0;
     return EVG_OK;
   }
@@ -632,6 +634,7 @@ evg_status evg_state_import(evg_ctx* c, const void* blob, uint64_t size) {
   }
   c->iters = got.iters;
   c->last_iter = got.last_iter;
+  c->messages_live = false;         // message buffers are scratch and are not part of the blob
   return EVG_OK;
 }
 

@@ -117,3 +117,42 @@ def test_first_event_later_than_iteration_zero(evg, oracle_mod):
     st = ring.stats(arrays=True)
     assert (st["events_full_rl"] <= 1).all() and st["events_topk"] > 0
     assert (st["events_full_rl"][:, [0, 2]] == 1).all()      # the large tensors did start sending
+
+
+def test_genuine_ties_fire_and_are_flagged(evg, oracle_mod):
+    """Scalar toy with exact arithmetic (lr = 0.5, gradient 1, h = 1): from iteration 2 on the
+    drift equals the adaptive threshold exactly, d == delta == 0.5.  The trigger is >=, so every
+    iteration fires, and both sides flag every test as a near tie."""
+    import torch
+    P = 3
+    x0 = np.zeros((P, 1), np.float32)
+    kw = dict(lr=0.5, momentum=0.0, grad_mode=1, thr_mode=1, horizon=1.0)
+    ring = evg.Ring(x0, [1], None, **kw)
+    orc = oracle_mod.Oracle(x0, np.array([1], np.uint64), None, **kw)
+    g = np.ones((P, 1), np.float32)
+    gd = torch.from_numpy(ring.layout.pad(g)).cuda()
+    for k in range(12):
+        ring.step(k, gd)
+        orc.step(k, grad=g)
+        a, b = ring.decisions(), orc.decisions()
+        for key in ("fired", "near_tie", "norm", "delta_before"):
+            assert np.array_equal(a[key], b[key]), (k, key)
+        assert a["fired"].all()
+        if k >= 2:
+            assert a["near_tie"].all() and (a["norm"] == 0.5).all() and (a["delta_before"] == 0.5).all()
+    assert ring.stats()["near_tie_flags"] == orc.totals()["near_tie_flags"] == P * 10
+    assert np.array_equal(ring.state("x"), orc.state("x"))
+
+
+@pytest.mark.parametrize("seed", [7, 20260303])
+@pytest.mark.parametrize("i", [2, 5])
+def test_other_seeds(evg, oracle_mod, i, seed):
+    """Configuration 2 (100 of its 500 iterations) and the narrow configuration 5 under two
+    more seeds: gradients, initial values and therefore every decision differ."""
+    from helpers import lockstep
+    w = inputs.reduced(i, seed=seed)
+    x0 = inputs.replicate(w.x0(), w.P)
+    ring = evg.Ring.from_workload(w, x0, mailbox_fill=float("nan"))
+    orc = oracle_mod.Oracle.from_workload(w, x0)
+    rep = lockstep(ring, orc, min(w.iters, 100), sample_messages=8)
+    assert all(rep["bitwise"].values())
