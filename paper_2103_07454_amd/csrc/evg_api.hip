@@ -430,9 +430,9 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
     HIP_TRY(launch_expand(t, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
   }
-  {
+  if (!a.delay) {      // with delayed delivery the mailboxes are written after the update
     Phase ph(c, EVG_PH_SEND_FULL);
-    HIP_TRY(launch_copy(t, c->chunk_elems, c->work_grid, !a.delay, c->stream));
+    HIP_TRY(launch_copy(t, c->chunk_elems, c->work_grid, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
   }
   if (a.topk_on) {

@@ -91,7 +91,7 @@ hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t dist, uint
 hipError_t launch_trigger(const Tables& t, const StepArgs& a, hipStream_t s);
 hipError_t launch_scan(const Tables& t, hipStream_t s);
 hipError_t launch_expand(const Tables& t, hipStream_t s);
-hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, bool mailboxes, hipStream_t s);
+hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s);
 hipError_t launch_deliver(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s);
 hipError_t launch_topk_select(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid,
                               hipStream_t s);

@@ -5,9 +5,8 @@
 //              at events (Eq. 3), marks the neighbours' mailbox slots as filled.
 //   k_scan     exclusive prefix sums of the fired flags weighted by chunk counts.
 //   k_expand   writes the compact lists of chunks to copy / to Top-K select.
-//   k_copy     x -> xhat, left neighbour's right mailbox, right neighbour's left
-//              mailbox for every listed chunk: the stand-in for the one-sided puts of
-//              Section 6.
+//   k_copy     x -> left neighbour's right mailbox, right neighbour's left mailbox for
+//              every listed chunk: the stand-in for the one-sided puts of Section 6.
 #include "evg_device.h"
 
 namespace evg {
@@ -121,8 +120,8 @@ __global__ __launch_bounds__(kThreads) void k_expand(Tables T) {
   for (uint32_t i = lane_id(); i < ld.nchunks; i += 64) dst[i] = first + i;
 }
 
-// MAILBOXES = false: only xhat takes the sent values now; the puts land later (k_deliver).
-template <int SWEEPS, bool MAILBOXES>
+// (xhat takes the sent values in the update pass, which has them in registers.)
+template <int SWEEPS>
 __global__ __launch_bounds__(kThreads) void k_copy(Tables T) {
   const uint32_t n = T.counts[0];
   for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
@@ -131,7 +130,6 @@ __global__ __launch_bounds__(kThreads) void k_copy(Tables T) {
     const ChunkDesc cd = T.chunks[c];
     const uint32_t left = (r + T.P - 1) % T.P, right = (r + 1) % T.P;
     const float* src = T.x + (size_t)r * T.Npad + cd.off;
-    float* d0 = T.xhat + (size_t)r * T.Npad + cd.off;
     float* d1 = T.mbox_r + (size_t)left * T.Npad + cd.off;
     float* d2 = T.mbox_l + (size_t)right * T.Npad + cd.off;
 #pragma unroll
@@ -139,11 +137,8 @@ __global__ __launch_bounds__(kThreads) void k_copy(Tables T) {
       const uint32_t e = it * kSweep + threadIdx.x * kLaneElems;
       if (e < cd.len) {
         const float4 v = ld4s(src + e);
-        st4s(d0 + e, v);
-        if (MAILBOXES) {
-          st4s(d1 + e, v);
-          st4s(d2 + e, v);
-        }
+        st4s(d1 + e, v);
+        st4s(d2 + e, v);
       }
     }
   }
@@ -197,13 +192,13 @@ __global__ __launch_bounds__(kThreads) void k_deliver(Tables T) {
   }
 }
 
-hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, bool mailboxes, hipStream_t s) {
+hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s) {
   const dim3 g(grid), b(kThreads);
   switch (chunk_elems / kSweep) {
-    case 1: if (mailboxes) k_copy<1, true><<<g, b, 0, s>>>(t); else k_copy<1, false><<<g, b, 0, s>>>(t); break;
-    case 2: if (mailboxes) k_copy<2, true><<<g, b, 0, s>>>(t); else k_copy<2, false><<<g, b, 0, s>>>(t); break;
-    case 4: if (mailboxes) k_copy<4, true><<<g, b, 0, s>>>(t); else k_copy<4, false><<<g, b, 0, s>>>(t); break;
-    case 8: if (mailboxes) k_copy<8, true><<<g, b, 0, s>>>(t); else k_copy<8, false><<<g, b, 0, s>>>(t); break;
+    case 1: k_copy<1><<<g, b, 0, s>>>(t); break;
+    case 2: k_copy<2><<<g, b, 0, s>>>(t); break;
+    case 4: k_copy<4><<<g, b, 0, s>>>(t); break;
+    case 8: k_copy<8><<<g, b, 0, s>>>(t); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -127,6 +127,7 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   const ChunkDesc cd = T.chunks[c];
   const uint32_t seg = r * T.L + cd.layer;
   const bool vl = T.valid_l[seg] != 0, vr = T.valid_r[seg] != 0;
+  const bool sent_whole = T.fired[seg] == 1;
   const size_t base = (size_t)r * T.Npad + cd.off;
   const float third = 0.333333343f;   // (float)(1/3): the ring's mixing weight
   const uint32_t e = sub * kSweep + threadIdx.x * kLaneElems;
@@ -142,7 +143,13 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
       va[0] = v4.x; va[1] = v4.y; va[2] = v4.z; va[3] = v4.w;
       if (vl) { const float4 t = ld4(T.mbox_l + base + e); la[0] = t.x; la[1] = t.y; la[2] = t.z; la[3] = t.w; }
       if (vr) { const float4 t = ld4(T.mbox_r + base + e); ra[0] = t.x; ra[1] = t.y; ra[2] = t.z; ra[3] = t.w; }
-      if (NORM == 1 || NORM == 3 || TOPK) { const float4 t = ld4(T.xhat + base + e); ha[0] = t.x; ha[1] = t.y; ha[2] = t.z; ha[3] = t.w; }
+      if (sent_whole) {
+        // the whole tensor was sent in this iteration: xhat becomes the x just read
+        ha[0] = xa[0]; ha[1] = xa[1]; ha[2] = xa[2]; ha[3] = xa[3];
+        st4(T.xhat + base + e, x4);
+      } else if (NORM == 1 || NORM == 3 || TOPK) {
+        const float4 t = ld4(T.xhat + base + e); ha[0] = t.x; ha[1] = t.y; ha[2] = t.z; ha[3] = t.w;
+      }
       if (GRADBUF) { const float4 t = ld4(A.grad + base + e); g[0] = t.x; g[1] = t.y; g[2] = t.z; g[3] = t.w; }
     }
     if (TOPK) {
