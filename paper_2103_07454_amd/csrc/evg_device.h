@@ -134,9 +134,13 @@ __device__ __forceinline__ void turn_cos_sin(float u, float& c, float& s) {
   cp = __builtin_fmaf(q, cp, 4.16666679e-2f);
   cp = __builtin_fmaf(q, cp, -0.5f);
   const float cs = __builtin_fmaf(q, cp, 1.0f);
-  const int quad = qi & 3;
-  c = quad == 0 ? cs : quad == 1 ? -sn : quad == 2 ? -cs : sn;
-  s = quad == 0 ? sn : quad == 1 ? cs : quad == 2 ? -sn : -cs;
+  // quarter turns: odd ones swap the two series; the signs follow from the quadrant
+  // (cos is negated in quadrants 1 and 2, sin in 2 and 3), applied as sign-bit flips
+  const uint32_t quad = (uint32_t)qi & 3u;
+  const bool swap = (quad & 1u) != 0;
+  const uint32_t cneg = ((quad + 1u) & 2u) << 30, sneg = (quad & 2u) << 30;
+  c = __uint_as_float(__float_as_uint(swap ? sn : cs) ^ cneg);
+  s = __uint_as_float(__float_as_uint(swap ? cs : sn) ^ sneg);
 }
 
 // Box-Muller on words (0,1) and (2,3): radius from the first, angle from the second.
