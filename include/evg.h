@@ -168,7 +168,9 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream);
  * (visible to every worker's update of the same iteration), then the averaging
  * and SGD update.  iter must be larger than the previous call's and below 2^31.
  * grad: DEVICE array laid out like x, required iff grad_mode == EVG_GRAD_BUFFER,
- * read during the step.  Asynchronous on the context's stream. */
+ * read during the step.  Asynchronous on the context's stream.  The iteration number
+ * and what depends on it travel as kernel arguments, so a captured HIP graph of this
+ * call must not be replayed for another iteration. */
 evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad);
 
 /* Waits for the stream, then fills *out (array members that are non-NULL too). */
