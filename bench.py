@@ -12,7 +12,8 @@ iterations 0..K-1 of the configuration, are timed with inputs resident in HBM.
 
 Prints one JSON line: throughput in parameter-elements/s, the roofline figures
 of the dominant kernel (the fused update pass, timed with HIP events on the
-stream it runs on) and the CPU oracle's throughput on a bounded sample.
+stream it runs on), per-step percentiles, what a plain triad reaches on the same
+box, and the CPU oracle's throughput on a bounded sample.
 """
 import argparse
 import json
@@ -104,10 +105,16 @@ def main():
     ring = make()                              # fresh state: timed steps are iterations 0..K-1
     if not args.no_phase_timers:
         ring.timing(True)
+    per_step = not args.no_phase_timers
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)] if per_step else []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
+        if per_step:
+            marks[k].record(ring.stream)
         ring.step(k, gbuf)
+    if per_step:
+        marks[args.steps].record(ring.stream)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -154,6 +161,11 @@ def main():
                            "avg_launch_ms": avg_ms, "launches": n_upd,
                            "algorithmic_bytes_per_launch": upd_bytes}
         out["phase_ms_per_step"] = {p: ms / max(1, args.steps) for p, (ms, n) in phases.items()}
+    if per_step:
+        # iterations 0 and 1 fire every tensor (forced first event, then a zero threshold)
+        ms = np.array([marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps)])
+        out["step_ms"] = {"median": float(np.median(ms)), "p10": float(np.percentile(ms, 10)),
+                          "p90": float(np.percentile(ms, 90)), "first_two": [float(v) for v in ms[:2]]}
     # the final model average (last line of Algorithm B): one pass over x of all workers
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ring.average()
@@ -167,6 +179,22 @@ def main():
     out["final_average"] = {"ms": avg_ms, "achieved_GBps": 4.0 * elems / (avg_ms * 1e-3) / 1e9}
     ring.close()
     del ring
+    torch.cuda.empty_cache()
+    # what a plain streaming kernel reaches on this machine: c = a + s*b over arrays of one arena's size
+    n_tri = max(elems, 1 << 26)
+    ta, tb, tc = (torch.full((n_tri,), float(i), device="cuda") for i in range(3))
+    torch.add(ta, tb, alpha=0.5, out=tc)
+    ev0.record()
+    for _ in range(avg_reps):
+        torch.add(ta, tb, alpha=0.5, out=tc)
+    ev1.record()
+    torch.cuda.synchronize()
+    tri = 12.0 * n_tri / (ev0.elapsed_time(ev1) / avg_reps * 1e-3) / 1e9
+    out["stream_triad"] = {"kind": "torch c = a + 0.5 b, fp32", "elements": n_tri, "GBps": tri,
+                           "frac_of_hbm_peak": tri / HBM_PEAK_GBS}
+    if "roofline" in out:
+        out["roofline"]["frac_of_triad"] = out["roofline"]["achieved"] / tri
+    del ta, tb, tc
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inputs, w)

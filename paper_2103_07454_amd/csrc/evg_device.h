@@ -68,6 +68,30 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* ws, ui
   return before + incl - v;
 }
 
+// The same over 64-bit words (several small counters packed into one).
+template <int W>
+__device__ __forceinline__ uint64_t block_excl_scan64(uint64_t v, uint64_t* ws, uint64_t* total) {
+  const uint32_t lane = lane_id();
+  uint64_t incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint64_t t = __shfl_up((unsigned long long)incl, o, 64);
+    if (lane >= (uint32_t)o) incl += t;
+  }
+  if (lane == 63) ws[wave_id()] = incl;
+  __syncthreads();
+  uint64_t before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < W; ++w) {
+    const uint64_t s = ws[w];
+    if ((uint32_t)w < wave_id()) before += s;
+    all += s;
+  }
+  __syncthreads();
+  *total = all;
+  return before + incl - v;
+}
+
 // ----------------------------------------------------------------------------
 // Synthetic gradients.  Philox4x32-10 (Salmon et al., SC'11): ten rounds, each
 // two 32x32->64 multiplies by fixed odd constants followed by xors with the

@@ -120,13 +120,14 @@ __global__ __launch_bounds__(kThreads) void k_topk_pick(Tables T) {
   }
 }
 
-// Two sweeps (8 elements per thread) share one workgroup scan, so that twice as many
-// loads are in flight between barriers.
+// Up to four sweeps (16 elements per thread) share one workgroup scan, so that more
+// loads are in flight between barriers: the four per-sweep counts travel as 16-bit
+// fields of one 64-bit word (a sweep stages at most 1024 entries).
 template <int SWEEPS>
 __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
-  constexpr int STEP = SWEEPS >= 2 ? 2 : 1;
+  constexpr int STEP = SWEEPS >= 4 ? 4 : SWEEPS;
   __shared__ uint32_t h[kHistBins];
-  __shared__ uint32_t ws[4];
+  __shared__ uint64_t ws[4];
   const uint32_t n = T.counts[1];
   for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
     const WorkItem wi = work_item(T, i);
@@ -148,6 +149,7 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
           if (!A.topk_key) h4[u] = ld4s(T.xhat + wi.base + e[u]);
         }
       }
+      uint64_t mine = 0;
 #pragma unroll
       for (int u = 0; u < STEP; ++u) {
         take[u] = 0;
@@ -164,25 +166,27 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
             if (kb == bin) atomicAdd(&h[(key[u][q] >> 9) & 2047u], 1u);
           }
         }
+        mine |= (uint64_t)__popc(take[u]) << (16 * u);
       }
       // staged order = index order: all of sweep `it` precedes sweep `it + 1`
-      const uint32_t c0 = __popc(take[0]), c1 = STEP == 2 ? __popc(take[STEP - 1]) : 0u;
-      uint32_t total;
-      const uint32_t ex = block_excl_scan<4>(c0 + (c1 << 16), ws, &total);
-      uint32_t pos[2] = {run + (ex & 0xFFFFu), run + (total & 0xFFFFu) + (ex >> 16)};
+      uint64_t total;
+      const uint64_t ex = block_excl_scan64<4>(mine, ws, &total);
+      uint32_t before = run;            // entries of this chunk's earlier sweeps
 #pragma unroll
       for (int u = 0; u < STEP; ++u) {
+        uint32_t pos = before + (uint32_t)((ex >> (16 * u)) & 0xFFFFu);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           if ((take[u] >> q) & 1u) {
-            T.stage_key[wi.base + pos[u]] = key[u][q];
-            T.stage_idx[wi.base + pos[u]] = wi.cd.j0 + e[u] + q;
-            T.stage_val[wi.base + pos[u]] = xa[u][q];
-            ++pos[u];
+            T.stage_key[wi.base + pos] = key[u][q];
+            T.stage_idx[wi.base + pos] = wi.cd.j0 + e[u] + q;
+            T.stage_val[wi.base + pos] = xa[u][q];
+            ++pos;
           }
         }
+        before += (uint32_t)((total >> (16 * u)) & 0xFFFFu);
       }
-      run += (total & 0xFFFFu) + (total >> 16);
+      run = before;
     }
     if (threadIdx.x == 0) T.stage_n[wi.w] = run;
     __syncthreads();
