@@ -106,7 +106,10 @@ typedef struct {
    * tensor l starts at r * padded_numel + offset_l (evg_layer_offsets).  x holds
    * the initial parameters at evg_init; the library then sets xhat := x and
    * vel := 0 and treats both mailboxes as empty (their contents are never read
-   * before a first message arrives). */
+   * before a first message arrives).  evg_init asks the runtime about each pointer:
+   * host memory, memory of another device, or an allocation that ends before the
+   * stated size gives EVG_ERR_INVALID (the same holds for evg_step's grad and
+   * evg_average's out). */
   float* x;      /* current parameters                                   */
   float* xhat;   /* values last sent (Section 4, X-hat)                   */
   float* mbox_l; /* last received from the left neighbour (r-1)           */

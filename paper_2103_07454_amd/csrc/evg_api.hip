@@ -138,6 +138,34 @@ evg_status check_layers(uint32_t L, const uint64_t* layer_numel) {
 
 bool finite_f(float v) { return std::isfinite(v); }
 
+// A kernel that is handed host memory, or an array shorter than the sizes say, faults
+// the GPU; so ask the runtime what `p` is.  The range test sees the whole allocation
+// `p` lies in (a sub-allocator's pool block counts as one), so it catches what runs
+// past that; where the runtime cannot name the range the test is skipped.
+evg_status check_device_array(const void* p, uint64_t bytes, const char* what) {
+  hipPointerAttribute_t at;
+  hipError_t e = hipPointerGetAttributes(&at, p);
+  if (e != hipSuccess || (at.type != hipMemoryTypeDevice && at.type != hipMemoryTypeManaged)) {
+    (void)hipGetLastError();   // a failed query must not surface after the next launch
+    return fail(EVG_ERR_INVALID, "%s does not point to device memory", what);
+  }
+  int dev = -1;
+  if (hipGetDevice(&dev) == hipSuccess && at.device != dev)
+    return fail(EVG_ERR_INVALID, "%s lives on device %d, the current device is %d", what, at.device, dev);
+  hipDeviceptr_t base = nullptr;
+  size_t size = 0;
+  e = hipMemGetAddressRange(&base, &size, const_cast<void*>(p));
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return EVG_OK;
+  }
+  const uintptr_t end = (uintptr_t)base + size;
+  if ((uintptr_t)p < (uintptr_t)base || (uintptr_t)p + bytes > end)
+    return fail(EVG_ERR_INVALID, "%s needs %llu bytes, its allocation ends after %llu", what,
+                (unsigned long long)bytes, (unsigned long long)(end - (uintptr_t)p));
+  return EVG_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -236,6 +264,9 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
       if (a < b + arena_bytes && b < a + arena_bytes)
         return fail(EVG_ERR_INVALID, "arenas %s and %s overlap", names[i], names[j]);
     }
+  // everything above is plain arithmetic; from here on the HIP runtime is involved
+  for (int i = 0; i < 5; ++i)
+    if ((st = check_device_array(arenas[i], arena_bytes, names[i])) != EVG_OK) return st;
 
   // ---- host tables --------------------------------------------------------
   evg_ctx* c = new (std::nothrow) evg_ctx();
@@ -390,6 +421,8 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   if (g.grad_mode == EVG_GRAD_BUFFER) {
     if (!grad) return fail(EVG_ERR_INVALID, "grad_mode is EVG_GRAD_BUFFER but grad is NULL");
     if ((uintptr_t)grad % 16) return fail(EVG_ERR_ALIGN, "grad is not 16-byte aligned");
+    evg_status gs = check_device_array(grad, (uint64_t)c->t.P * c->t.Npad * 4, "grad");
+    if (gs != EVG_OK) return gs;
   }
   StepArgs a{};
   a.k = (uint32_t)iter;
@@ -540,6 +573,8 @@ evg_status evg_message(evg_ctx* c, uint32_t r, uint32_t l, uint32_t* idx, float*
 evg_status evg_average(evg_ctx* c, float* out) {
   if (!c || !out) return fail(EVG_ERR_INVALID, "context and out must be non-NULL");
   if ((uintptr_t)out % 16) return fail(EVG_ERR_ALIGN, "out is not 16-byte aligned");
+  evg_status st = check_device_array(out, c->t.Npad * 4, "out");
+  if (st != EVG_OK) return st;
   HIP_TRY(launch_average(c->t, out, c->stream));
   return EVG_OK;
 }

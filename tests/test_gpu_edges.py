@@ -156,3 +156,35 @@ def test_other_seeds(evg, oracle_mod, i, seed):
     orc = oracle_mod.Oracle.from_workload(w, x0)
     rep = lockstep(ring, orc, min(w.iters, 100), sample_messages=8)
     assert all(rep["bitwise"].values())
+
+
+def test_wrong_memory_is_refused_before_any_launch(evg):
+    """Host memory, or a device array shorter than the sizes say, would fault a kernel:
+    the library asks the runtime and returns an error instead."""
+    import ctypes as C
+    import torch
+    w = inputs.reduced(3)                                   # 16 workers, about 11 MB per arena
+    ring = evg.Ring.from_workload(w, grad_mode=evg.GRAD_BUFFER)
+    npad = ring.layout.npad
+    host = np.zeros(w.P * npad, np.float32)
+
+    class HostPtr:
+        def data_ptr(self):
+            return host.ctypes.data
+    with pytest.raises(evg.EvgError) as e:
+        ring.step(0, HostPtr())
+    assert e.value.status == 1 and "device memory" in str(e.value)
+    small = torch.zeros(1024, device="cuda")                # its pool block ends long before P * npad floats
+    with pytest.raises(evg.EvgError) as e:
+        ring.step(0, small)
+    assert e.value.status == 1 and "allocation ends" in str(e.value)
+    with pytest.raises(evg.EvgError):
+        evg._check(evg.lib().evg_average(ring._h, C.c_void_p(host.ctypes.data)))
+    # the refused calls left nothing behind: the same context still steps, bit for bit like a fresh one
+    g = torch.from_numpy(ring.layout.pad(inputs.random_grads(w.P, w.N, 3, 0.01))).cuda()
+    other = evg.Ring.from_workload(w, grad_mode=evg.GRAD_BUFFER)
+    for k in range(3):
+        ring.step(k, g)
+        other.step(k, g)
+    assert np.array_equal(ring.state("x"), other.state("x"))
+    assert ring.stats()["iters"] == 3

@@ -307,16 +307,3 @@ def test_reduced_width_configs_full_length(evg, oracle_mod, i):
     print(f"  messages {100 * st['events_total'] / st['regular_events']:.1f}% of regular, "
           f"communication {100 * (st['value_words'] + st['index_words']) / st['regular_words']:.1f}%")
     assert rep["rel"]["x"] <= 1e-5
-
-
-@pytest.mark.parametrize("seed", [1, 20210312])
-def test_other_seeds(evg, oracle_mod, seed):
-    """Configuration 1 and the narrow configuration 5 under two more seeds (initial
-    parameters and gradient streams both change)."""
-    from helpers import lockstep
-    for w in (inputs.config(1, seed), inputs.reduced(5, seed)):
-        ring, orc = pair(evg, oracle_mod, w)
-        rep = lockstep(ring, orc, w.iters, sample_messages=8)
-        note(f"{w.name}/seed {seed}", rep)
-        assert rep["rel"]["x"] <= 1e-5
-        ring.close()
