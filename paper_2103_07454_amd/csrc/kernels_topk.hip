@@ -205,7 +205,7 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
   return __popcll(mask & ((1ull << lane_id()) - 1ull));
 }
 
-constexpr int kBatch = 4;    // 64-entry groups loaded together by a wavefront, to overlap their latency
+constexpr int kBatch = 8;    // 64-entry groups loaded together by a wavefront, to overlap their latency
 
 // Bits 8..0 of the staged keys that carry the 22-bit prefix found so far.  Matches are
 // rare (a 2^-22 slice of the key range), so they go straight to the tensor's histogram,
@@ -303,6 +303,7 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
     uint32_t per_sweep[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // winners per sweep (wave-uniform)
     for (uint32_t q0 = 0; q0 < ns; q0 += 64 * kBatch) {
       uint32_t key[kBatch], j[kBatch];
+      float val[kBatch];
       bool in[kBatch];
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
@@ -310,6 +311,7 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
         in[u] = q < ns;
         key[u] = in[u] ? T.stage_key[wi.base + q] : 0u;
         j[u] = in[u] ? T.stage_idx[wi.base + q] : wi.cd.j0;
+        val[u] = in[u] ? T.stage_val[wi.base + q] : 0.0f;   // most staged entries win: fetch with the keys
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {                // groups in index order
@@ -320,7 +322,7 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
         if (win) {
           const uint32_t pos = g + (eq < ties ? eq : ties);
           T.msg_idx[mbase + pos] = j[u];
-          T.msg_val[mbase + pos] = T.stage_val[wi.base + q0 + u * 64 + lane_id()];
+          T.msg_val[mbase + pos] = val[u];
         }
         const uint32_t sw = (j[u] - wi.cd.j0) / (uint32_t)kSweep;
 #pragma unroll
