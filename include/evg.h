@@ -48,6 +48,7 @@ enum { EVG_GRAD_SYNTH = 0, EVG_GRAD_BUFFER = 1 };
 enum { EVG_DIST_NORMAL = 0, EVG_DIST_STUDENT_T3 = 1 };
 enum { EVG_NORM_FUSED = 0, EVG_NORM_SEPARATE = 1 };
 enum { EVG_TRIGGER_DRIFT_NORM = 0, EVG_TRIGGER_NORM_DIFF = 1 };
+enum { EVG_ACCESS_AUTO = 0, EVG_ACCESS_STREAM = 1, EVG_ACCESS_CACHED = 2 };
 
 /* Synthetic gradients (they replace Algorithm B's "compute the local stochastic
  * gradient"): element j of tensor l of worker r at iteration k is
@@ -100,6 +101,11 @@ typedef struct {
                                    sent in; 1: it lands after them and is used from the next
                                    iteration on (a deterministic stand-in for the asynchrony of
                                    one-sided puts, Section 7)                                 */
+  uint32_t access_mode;         /* how the dense passes touch the arenas; results never differ.
+                                   EVG_ACCESS_STREAM: non-temporal (rings far larger than the
+                                   caches); EVG_ACCESS_CACHED: ordinary accesses (rings that fit
+                                   the 256 MB last-level cache); EVG_ACCESS_AUTO: cached if the
+                                   five arenas together take at most 128 MB                    */
   evg_synth synth;
   /* DEVICE arenas owned by the caller, each P * evg_padded_numel() floats,
    * 16-byte aligned, non-overlapping, alive until evg_destroy.  Worker r's

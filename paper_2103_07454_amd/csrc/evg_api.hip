@@ -57,6 +57,7 @@ struct evg_ctx {
   uint64_t iters = 0;
   int64_t last_iter = -1;
   bool messages_live = false;       // the message buffers hold the last step's messages
+  bool cached = false;              // the five arenas together fit the last-level cache
   // timing
   bool timing = false;
   std::vector<TimerPair> pending;
@@ -234,6 +235,7 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   if (cfg->norm_mode > EVG_NORM_SEPARATE) return fail(EVG_ERR_INVALID, "unknown norm_mode %u", cfg->norm_mode);
   if (cfg->trigger_kind > EVG_TRIGGER_NORM_DIFF) return fail(EVG_ERR_INVALID, "unknown trigger_kind %u", cfg->trigger_kind);
   if (cfg->delivery_delay > 1) return fail(EVG_ERR_INVALID, "delivery_delay must be 0 or 1");
+  if (cfg->access_mode > EVG_ACCESS_CACHED) return fail(EVG_ERR_INVALID, "unknown access_mode %u", cfg->access_mode);
   const uint32_t ce = cfg->chunk_elems ? cfg->chunk_elems : 8192u;
   if (ce != 1024 && ce != 2048 && ce != 4096 && ce != 8192)
     return fail(EVG_ERR_INVALID, "chunk_elems must be 0, 1024, 2048, 4096 or 8192");
@@ -349,6 +351,10 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   } while (0)
   HIP_OR_FREE(hipGetDevice(&dev));
   HIP_OR_FREE(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  // 256 MB of last-level cache on MI355X; a ring whose arenas take at most half of it is
+  // served from there and does better with ordinary than with streaming accesses
+  c->cached = cfg->access_mode == EVG_ACCESS_CACHED ||
+              (cfg->access_mode == EVG_ACCESS_AUTO && 5 * arena_bytes <= (128ull << 20));
   const uint64_t full_grid = (uint64_t)P * C;
   c->work_grid = (uint32_t)(full_grid < (uint64_t)cus * 8 ? full_grid : (uint64_t)cus * 8);
   TRY_OR_FREE(c->dalloc(&d_chunks, C, false));
@@ -435,6 +441,7 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   a.topk_key = g.topk_key;
   a.delay = g.delivery_delay;
   a.hist_fused = (g.topk_ppm && g.norm_mode == EVG_NORM_FUSED) ? 1u : 0u;
+  a.cached = c->cached ? 1u : 0u;
   const bool norm_diff = g.trigger_kind == EVG_TRIGGER_NORM_DIFF;
   // fused + whole-tensor sends: xhat's norm is a scalar per tensor and xhat is never read
   a.norm_src = !norm_diff ? 0u : (g.norm_mode == EVG_NORM_FUSED && !g.topk_ppm) ? 1u : 2u;
@@ -465,7 +472,7 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   }
   if (!a.delay) {      // with delayed delivery the mailboxes are written after the update
     Phase ph(c, EVG_PH_SEND_FULL);
-    HIP_TRY(launch_copy(t, c->chunk_elems, c->work_grid, c->stream));
+    HIP_TRY(launch_copy(t, a, c->chunk_elems, c->work_grid, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
   }
   if (a.topk_on) {

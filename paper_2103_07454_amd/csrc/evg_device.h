@@ -92,6 +92,20 @@ __device__ __forceinline__ uint64_t block_excl_scan64(uint64_t v, uint64_t* ws, 
   return before + incl - v;
 }
 
+// The same accesses with the choice left to the caller: a ring whose arenas fit the
+// last-level cache is better served by ordinary cached accesses (measured 10 % per step
+// on an 8-worker ResNet-20-sized ring).
+template <bool STREAM>
+__device__ __forceinline__ float4 ld4t(const float* p) {
+  if (STREAM) return ld4s(p);
+  return *reinterpret_cast<const float4*>(p);
+}
+template <bool STREAM>
+__device__ __forceinline__ void st4t(float* p, float4 a) {
+  if (STREAM) st4s(p, a);
+  else *reinterpret_cast<float4*>(p) = a;
+}
+
 // ----------------------------------------------------------------------------
 // Synthetic gradients.  Philox4x32-10 (Salmon et al., SC'11): ten rounds, each
 // two 32x32->64 multiplies by fixed odd constants followed by xors with the

@@ -77,6 +77,7 @@ struct StepArgs {
                            // and squared xhat in partials / partials_hat
   uint32_t delay;          // messages of this iteration land after its updates
   uint32_t hist_fused;     // the update pass of the previous iteration already built pass A's histograms
+  uint32_t cached;         // the arenas fit the last-level cache: ordinary instead of streaming accesses
   uint32_t key0, key1;
   double decay_pow;        // decay^k
   float spike_prob, spike_gain;
@@ -91,7 +92,7 @@ hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t dist, uint
 hipError_t launch_trigger(const Tables& t, const StepArgs& a, hipStream_t s);
 hipError_t launch_scan(const Tables& t, hipStream_t s);
 hipError_t launch_expand(const Tables& t, hipStream_t s);
-hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s);
+hipError_t launch_copy(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid, hipStream_t s);
 hipError_t launch_deliver(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s);
 hipError_t launch_topk_select(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid,
                               hipStream_t s);

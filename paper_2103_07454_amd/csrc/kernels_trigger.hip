@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kThreads) void k_expand(Tables T) {
 }
 
 // (xhat takes the sent values in the update pass, which has them in registers.)
-template <int SWEEPS>
+template <int SWEEPS, bool STREAM>
 __global__ __launch_bounds__(kThreads) void k_copy(Tables T) {
   const uint32_t n = T.counts[0];
   for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
@@ -136,9 +136,9 @@ __global__ __launch_bounds__(kThreads) void k_copy(Tables T) {
     for (int it = 0; it < SWEEPS; ++it) {
       const uint32_t e = it * kSweep + threadIdx.x * kLaneElems;
       if (e < cd.len) {
-        const float4 v = ld4s(src + e);
-        st4s(d1 + e, v);
-        st4s(d2 + e, v);
+        const float4 v = ld4t<STREAM>(src + e);
+        st4t<STREAM>(d1 + e, v);
+        st4t<STREAM>(d2 + e, v);
       }
     }
   }
@@ -192,16 +192,21 @@ __global__ __launch_bounds__(kThreads) void k_deliver(Tables T) {
   }
 }
 
-hipError_t launch_copy(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s) {
+template <bool STREAM>
+static hipError_t launch_copy_v(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s) {
   const dim3 g(grid), b(kThreads);
   switch (chunk_elems / kSweep) {
-    case 1: k_copy<1><<<g, b, 0, s>>>(t); break;
-    case 2: k_copy<2><<<g, b, 0, s>>>(t); break;
-    case 4: k_copy<4><<<g, b, 0, s>>>(t); break;
-    case 8: k_copy<8><<<g, b, 0, s>>>(t); break;
+    case 1: k_copy<1, STREAM><<<g, b, 0, s>>>(t); break;
+    case 2: k_copy<2, STREAM><<<g, b, 0, s>>>(t); break;
+    case 4: k_copy<4, STREAM><<<g, b, 0, s>>>(t); break;
+    case 8: k_copy<8, STREAM><<<g, b, 0, s>>>(t); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+hipError_t launch_copy(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid, hipStream_t s) {
+  return a.cached ? launch_copy_v<false>(t, chunk_elems, grid, s) : launch_copy_v<true>(t, chunk_elems, grid, s);
 }
 
 hipError_t launch_deliver(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s) {

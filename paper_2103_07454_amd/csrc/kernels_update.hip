@@ -19,7 +19,6 @@
 namespace evg {
 
 __device__ __forceinline__ float4 ld4(const float* p) { return ld4s(p); }
-__device__ __forceinline__ void st4(float* p, float4 v) { st4s(p, v); }
 
 // Squared drift of the first nv lanes of a float4 pair, added in lane order.
 __device__ __forceinline__ void drift_acc(double& acc, const float x[4], const float h[4], uint32_t nv) {
@@ -135,7 +134,8 @@ __device__ __forceinline__ void block_sums(const double v[SPW], double* ws, doub
 // SPW: consecutive sweeps of a chunk per workgroup (one float4 per thread and sweep).  One
 // streams best; two halve the per-workgroup costs of the Top-K work (message look-up,
 // barriers, clearing and merging the histogram).
-template <int DIST, bool GRADBUF, int NORM, bool TOPK, bool HISTA, int SPW>
+// STREAM: non-temporal accesses to the arenas (rings larger than the last-level cache).
+template <int DIST, bool GRADBUF, int NORM, bool TOPK, bool HISTA, int SPW, bool STREAM>
 __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   __shared__ double ws[4 * SPW];
   // LDS: the windows of the three patches; once those are consumed the same
@@ -170,19 +170,19 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) { xa[u][i] = 0.f; va[u][i] = 0.f; la[u][i] = 0.f; ra[u][i] = 0.f; ha[u][i] = 0.f; g[u][i] = 0.f; }
       if (live[u]) {
-        const float4 x4 = ld4(T.x + base + e[u]), v4 = ld4(T.vel + base + e[u]);
+        const float4 x4 = ld4t<STREAM>(T.x + base + e[u]), v4 = ld4t<STREAM>(T.vel + base + e[u]);
         xa[u][0] = x4.x; xa[u][1] = x4.y; xa[u][2] = x4.z; xa[u][3] = x4.w;
         va[u][0] = v4.x; va[u][1] = v4.y; va[u][2] = v4.z; va[u][3] = v4.w;
-        if (vl) { const float4 t = ld4(T.mbox_l + base + e[u]); la[u][0] = t.x; la[u][1] = t.y; la[u][2] = t.z; la[u][3] = t.w; }
-        if (vr) { const float4 t = ld4(T.mbox_r + base + e[u]); ra[u][0] = t.x; ra[u][1] = t.y; ra[u][2] = t.z; ra[u][3] = t.w; }
+        if (vl) { const float4 t = ld4t<STREAM>(T.mbox_l + base + e[u]); la[u][0] = t.x; la[u][1] = t.y; la[u][2] = t.z; la[u][3] = t.w; }
+        if (vr) { const float4 t = ld4t<STREAM>(T.mbox_r + base + e[u]); ra[u][0] = t.x; ra[u][1] = t.y; ra[u][2] = t.z; ra[u][3] = t.w; }
         if (sent_whole) {
           // the whole tensor was sent in this iteration: xhat becomes the x just read
           ha[u][0] = xa[u][0]; ha[u][1] = xa[u][1]; ha[u][2] = xa[u][2]; ha[u][3] = xa[u][3];
-          st4(T.xhat + base + e[u], x4);
+          st4t<STREAM>(T.xhat + base + e[u], x4);
         } else if (NORM == 1 || NORM == 3 || TOPK) {
-          const float4 t = ld4(T.xhat + base + e[u]); ha[u][0] = t.x; ha[u][1] = t.y; ha[u][2] = t.z; ha[u][3] = t.w;
+          const float4 t = ld4t<STREAM>(T.xhat + base + e[u]); ha[u][0] = t.x; ha[u][1] = t.y; ha[u][2] = t.z; ha[u][3] = t.w;
         }
-        if (GRADBUF) { const float4 t = ld4(A.grad + base + e[u]); g[u][0] = t.x; g[u][1] = t.y; g[u][2] = t.z; g[u][3] = t.w; }
+        if (GRADBUF) { const float4 t = ld4t<STREAM>(A.grad + base + e[u]); g[u][0] = t.x; g[u][1] = t.y; g[u][2] = t.z; g[u][3] = t.w; }
       }
     }
     if (TOPK) {
@@ -206,9 +206,9 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
           const uint32_t b0 = take_patch(pv, pm, u, ha[u]);
           const uint32_t b1 = take_patch(pv + kWin, pm + kWinWords, u, la[u]);
           const uint32_t b2 = take_patch(pv + 2 * kWin, pm + 2 * kWinWords, u, ra[u]);
-          if (live[u] && b0) st4(T.xhat + base + e[u], make_float4(ha[u][0], ha[u][1], ha[u][2], ha[u][3]));
-          if (live[u] && b1) st4(T.mbox_l + base + e[u], make_float4(la[u][0], la[u][1], la[u][2], la[u][3]));
-          if (live[u] && b2) st4(T.mbox_r + base + e[u], make_float4(ra[u][0], ra[u][1], ra[u][2], ra[u][3]));
+          if (live[u] && b0) st4t<STREAM>(T.xhat + base + e[u], make_float4(ha[u][0], ha[u][1], ha[u][2], ha[u][3]));
+          if (live[u] && b1) st4t<STREAM>(T.mbox_l + base + e[u], make_float4(la[u][0], la[u][1], la[u][2], la[u][3]));
+          if (live[u] && b2) st4t<STREAM>(T.mbox_r + base + e[u], make_float4(ra[u][0], ra[u][1], ra[u][2], ra[u][3]));
         }
       }
     }
@@ -254,8 +254,8 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
             va[u][i] = vn;
           }
         }
-        st4(T.x + base + e[u], make_float4(xa[u][0], xa[u][1], xa[u][2], xa[u][3]));
-        st4(T.vel + base + e[u], make_float4(va[u][0], va[u][1], va[u][2], va[u][3]));
+        st4t<STREAM>(T.x + base + e[u], make_float4(xa[u][0], xa[u][1], xa[u][2], xa[u][3]));
+        st4t<STREAM>(T.vel + base + e[u], make_float4(va[u][0], va[u][1], va[u][2], va[u][3]));
         if (NORM == 1) drift_acc(acc[u], xa[u], ha[u], nv);
         if (NORM >= 2) square_acc(acc[u], xa[u], nv);
         if (NORM == 3) square_acc(acc_hat[u], ha[u], nv);
@@ -303,7 +303,7 @@ __global__ __launch_bounds__(kThreads) void k_average(Tables T, float* out) {
     a0 += (double)v.x; a1 += (double)v.y; a2 += (double)v.z; a3 += (double)v.w;
   }
   const double p = (double)T.P;
-  st4(out + q * 4, make_float4((float)(a0 / p), (float)(a1 / p), (float)(a2 / p), (float)(a3 / p)));
+  st4s(out + q * 4, make_float4((float)(a0 / p), (float)(a1 / p), (float)(a2 / p), (float)(a3 / p)));
 }
 
 hipError_t launch_norm(const Tables& t, bool norm_diff, hipStream_t s) {
@@ -317,9 +317,15 @@ template <int NORM, bool TOPK, bool HISTA, int SPW>
 static void launch_update_w(const Tables& t, const StepArgs& a, uint32_t dist, uint32_t grad_mode,
                             hipStream_t s) {
   const dim3 grid(t.C * (t.SW / SPW), t.P), block(kThreads);
-  if (grad_mode == 1) k_update<0, true, NORM, TOPK, HISTA, SPW><<<grid, block, 0, s>>>(t, a);
-  else if (dist == 0) k_update<0, false, NORM, TOPK, HISTA, SPW><<<grid, block, 0, s>>>(t, a);
-  else k_update<1, false, NORM, TOPK, HISTA, SPW><<<grid, block, 0, s>>>(t, a);
+  if (a.cached) {
+    if (grad_mode == 1) k_update<0, true, NORM, TOPK, HISTA, SPW, false><<<grid, block, 0, s>>>(t, a);
+    else if (dist == 0) k_update<0, false, NORM, TOPK, HISTA, SPW, false><<<grid, block, 0, s>>>(t, a);
+    else k_update<1, false, NORM, TOPK, HISTA, SPW, false><<<grid, block, 0, s>>>(t, a);
+    return;
+  }
+  if (grad_mode == 1) k_update<0, true, NORM, TOPK, HISTA, SPW, true><<<grid, block, 0, s>>>(t, a);
+  else if (dist == 0) k_update<0, false, NORM, TOPK, HISTA, SPW, true><<<grid, block, 0, s>>>(t, a);
+  else k_update<1, false, NORM, TOPK, HISTA, SPW, true><<<grid, block, 0, s>>>(t, a);
 }
 
 template <int NORM, bool TOPK, bool HISTA>

@@ -22,7 +22,8 @@ def spec(sizes):
 def run(evg, oracle_mod, w, iters, gpu=None, **over):
     from helpers import lockstep
     x0 = inputs.replicate(w.x0(), w.P)
-    ring = evg.Ring.from_workload(w, x0, mailbox_fill=float("nan"), **over, **(gpu or {}))
+    gpu = {"access_mode": evg.ACCESS_STREAM, **(gpu or {})}     # the kernels the large rings use
+    ring = evg.Ring.from_workload(w, x0, mailbox_fill=float("nan"), **over, **gpu)
     orc = oracle_mod.Oracle.from_workload(w, x0, **over)
     rep = lockstep(ring, orc, iters, sample_messages=64)
     assert all(rep["bitwise"].values()), rep

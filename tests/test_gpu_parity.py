@@ -24,7 +24,10 @@ def evg():
 def pair(evg, oracle_mod, w, x0=None, gpu=None, **over):
     if x0 is None:
         x0 = inputs.replicate(w.x0(), w.P)
-    ring = evg.Ring.from_workload(w, x0, mailbox_fill=float("nan"), **over, **(gpu or {}))
+    # small rings would default to cached accesses: these tests run the streaming kernels,
+    # the ones the large configurations use, unless a test asks otherwise
+    gpu = {"access_mode": evg.ACCESS_STREAM, **(gpu or {})}
+    ring = evg.Ring.from_workload(w, x0, mailbox_fill=float("nan"), **over, **gpu)
     orc = oracle_mod.Oracle.from_workload(w, x0, **over)
     return ring, orc
 
@@ -187,6 +190,20 @@ def test_delayed_delivery(evg, oracle_mod, mode):
     note(f"delayed/{mode}", rep)
     assert all(rep["bitwise"].values())
     assert 0 < ring.stats()["events_total"] < ring.stats()["regular_events"]
+
+
+@pytest.mark.parametrize("access", ["stream", "cached"])
+@pytest.mark.parametrize("mode", ["whole", "topk"])
+def test_streaming_and_cached_accesses(evg, oracle_mod, mode, access):
+    """Small rings default to cached accesses, large ones to non-temporal ones: both
+    kernel variants against the oracle on the same ring."""
+    from helpers import lockstep
+    w = ragged(topk_ppm=100_000 if mode == "topk" else 0)
+    am = evg.ACCESS_STREAM if access == "stream" else evg.ACCESS_CACHED
+    ring, orc = pair(evg, oracle_mod, w, gpu=dict(access_mode=am))
+    assert ring.access_mode == am
+    rep = lockstep(ring, orc, w.iters, sample_messages=32)
+    assert all(rep["bitwise"].values())
 
 
 def test_separate_norm_pass_matches_fused(evg):
