@@ -163,6 +163,31 @@ def test_buffer_gradients_and_history(evg, oracle_mod):
     assert all(rep["bitwise"].values())
 
 
+@pytest.mark.parametrize("chunk", [1024, 8192])
+def test_buffer_gradients_with_topk(evg, oracle_mod, chunk):
+    """Caller-supplied gradients together with Top-K messages (the update pass variant
+    that reads a gradient arena while it applies the three patches)."""
+    import torch
+    from helpers import lockstep
+    w = ragged(topk_ppm=100_000)
+    ring, orc = pair(evg, oracle_mod, w, gpu=dict(chunk_elems=chunk), grad_mode=1)
+    lay = ring.layout
+    keep = []
+
+    def host(k):
+        return inputs.random_grads(w.P, w.N, 500 + k, 0.02 * 0.97 ** k)
+
+    def dev(k):
+        keep.append(torch.from_numpy(lay.pad(host(k))).cuda())
+        return keep[-1]
+
+    rep = lockstep(ring, orc, 30, grads=host, gpu_grads=dev, sample_messages=32)
+    note(f"buffer/topk/{chunk}", rep)
+    st = ring.stats()
+    assert st["events_topk"] > 0 and st["events_total"] < st["regular_events"]
+    assert all(rep["bitwise"].values())
+
+
 @pytest.mark.parametrize("mode", ["whole_fused", "topk_fused", "whole_separate", "topk_separate"])
 def test_norm_difference_trigger(evg, oracle_mod, mode):
     """Trigger on | ||x|| - ||xhat|| | (the wording of Section 4) instead of || x - xhat ||."""
