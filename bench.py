@@ -69,6 +69,8 @@ def main():
                          "1 = difference of the norms")
     ap.add_argument("--delivery-delay", type=int, default=0,
                     help="1 = messages land after the iteration's updates (not a benchmark configuration)")
+    ap.add_argument("--xhat-reset", type=int, default=0,
+                    help="1 = a Top-K event resets the whole tensor's xhat (not a benchmark configuration)")
     ap.add_argument("--diag-grad-buffer", action="store_true",
                     help="diagnostic only (not the named workload): gradients from a fixed device buffer")
     args = ap.parse_args()
@@ -90,9 +92,10 @@ def main():
     def make():
         if args.diag_grad_buffer:
             return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk, grad_mode=evg.GRAD_BUFFER,
-                                          trigger_kind=args.trigger_kind, delivery_delay=args.delivery_delay)
+                                          trigger_kind=args.trigger_kind, delivery_delay=args.delivery_delay,
+                                          xhat_reset=args.xhat_reset)
         return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk, trigger_kind=args.trigger_kind,
-                                      delivery_delay=args.delivery_delay)
+                                      delivery_delay=args.delivery_delay, xhat_reset=args.xhat_reset)
 
     ring = make()
     if args.diag_grad_buffer:
@@ -150,7 +153,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name + ("+DIAG_GRAD_BUFFER" if args.diag_grad_buffer else "")
                    + ("+NORM_DIFF_TRIGGER" if args.trigger_kind else "")
-                   + ("+DELAYED_DELIVERY" if args.delivery_delay else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
+                   + ("+DELAYED_DELIVERY" if args.delivery_delay else "")
+                   + ("+XHAT_RESET" if args.xhat_reset else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
                    "threshold": "adaptive" if w.thr_mode else "fixed", "topk_ppm": w.topk_ppm,
                    "chunk_elems": args.chunk or 8192,
                    "fraction_fired_full": f_full, "fraction_fired_topk": f_topk,

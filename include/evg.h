@@ -101,6 +101,12 @@ typedef struct {
                                    sent in; 1: it lands after them and is used from the next
                                    iteration on (a deterministic stand-in for the asynchrony of
                                    one-sided puts, Section 7)                                 */
+  uint32_t xhat_reset;          /* what a Top-K event does to xhat.  0: only the sent entries take
+                                   the sent values (they are what was communicated).  1: the
+                                   whole tensor's xhat becomes x, as after a whole send (the
+                                   per-tensor xhat of Section 4 read literally); the mailboxes
+                                   still change only at the sent indices.  Not available
+                                   together with delivery_delay = 1                            */
   uint32_t access_mode;         /* how the dense passes touch the arenas; results never differ.
                                    EVG_ACCESS_STREAM: non-temporal (rings far larger than the
                                    caches); EVG_ACCESS_CACHED: ordinary accesses (rings that fit

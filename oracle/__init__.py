@@ -39,7 +39,7 @@ class OrcConfig(C.Structure):
         ("seed", C.c_uint64), ("dist", C.c_uint32), ("fan_in_scaling", C.c_uint32),
         ("sigma0", C.c_double), ("decay", C.c_double),
         ("spike_prob", C.c_float), ("spike_gain", C.c_float),
-        ("delivery_delay", C.c_uint32),
+        ("delivery_delay", C.c_uint32), ("xhat_reset", C.c_uint32),
     ]
 
 
@@ -98,7 +98,7 @@ class Oracle:
                  thr_mode=1, thr_fixed=0.0, horizon=1.0, hist_len=1, delta_init=0.0,
                  force_first=1, topk_ppm=0, topk_key=0, trigger_kind=0, grad_mode=0,
                  seed=0, dist=0, fan_in_scaling=0, sigma0=0.0, decay=1.0,
-                 spike_prob=0.0, spike_gain=1.0, delivery_delay=0):
+                 spike_prob=0.0, spike_gain=1.0, delivery_delay=0, xhat_reset=0):
         self._h = None
         x0 = np.ascontiguousarray(x0, dtype=np.float32)
         self.P, self.N = x0.shape
@@ -111,7 +111,7 @@ class Oracle:
                         lr, momentum, thr_mode, thr_fixed, horizon, hist_len, delta_init,
                         force_first, topk_ppm, topk_key, trigger_kind, grad_mode,
                         seed, dist, fan_in_scaling, sigma0, decay, spike_prob, spike_gain,
-                        delivery_delay)
+                        delivery_delay, xhat_reset)
         self._h = lib().orc_create(C.byref(cfg), _p(x0, C.c_float))
         if not self._h:
             raise ValueError("oracle rejected the configuration")

@@ -39,6 +39,10 @@
 //   R9  delivery_delay = 1 is a deterministic stand-in for the asynchrony of one-sided
 //       puts (Section 7 blames it for threshold oscillations): what is sent in iteration
 //       k is written into the neighbours' memory only after iteration k's updates.
+//   R10 xhat_reset = 1 is the other reading of "previously communicated values" after a
+//       Top-K event (Section 4 defines xhat per tensor, Section 7 sends only part of it):
+//       the whole tensor's xhat becomes x, as after a whole send, while the receivers'
+//       copies still change only at the sent indices.
 //   R8  gradients are synthetic: a counter-based Philox4x32-10 stream turned
 //       into normals by Box-Muller with fixed polynomial log/sin/cos.
 //
@@ -81,6 +85,8 @@ struct orc_config {
   float spike_prob, spike_gain;
   uint32_t delivery_delay;       // 0: a message is visible to the same iteration's updates;
                                  // 1: it arrives after them (visible from the next iteration)
+  uint32_t xhat_reset;           // what a Top-K event does to xhat: 0 only the sent entries take
+                                 // the sent values (R6), 1 the whole tensor is reset to x (R10)
 };
 
 }  // extern "C"
@@ -277,7 +283,7 @@ void orc_topk_select(const uint32_t* keys, uint64_t n, uint64_t K, uint32_t* out
 
 void* orc_create(const orc_config* cfg, const float* x0) {
   if (!cfg || !x0 || cfg->P < 3 || cfg->L < 1 || !cfg->layer_numel) return nullptr;
-  if (cfg->hist_len < 1 || cfg->delivery_delay > 1) return nullptr;
+  if (cfg->hist_len < 1 || cfg->delivery_delay > 1 || cfg->xhat_reset > 1) return nullptr;
   Oracle* o = new Oracle();
   o->cfg = *cfg;
   o->numel.assign(cfg->layer_numel, cfg->layer_numel + cfg->L);
@@ -397,6 +403,8 @@ int orc_step(void* h, uint64_t k, const float* grad_or_null, const int8_t* overr
           hs[j] = xs[j];
           if (now) { toR[j] = xs[j]; toL[j] = xs[j]; }
         }
+        if (c.xhat_reset)
+          for (uint64_t j = 0; j < n; ++j) hs[j] = xs[j];
         if (!now) o.in_flight.push_back({s, false, o.msg_idx[s], o.msg_val[s]});
         o.fired[s] = 2; o.ev_topk[s]++;
       }

@@ -235,6 +235,9 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   if (cfg->norm_mode > EVG_NORM_SEPARATE) return fail(EVG_ERR_INVALID, "unknown norm_mode %u", cfg->norm_mode);
   if (cfg->trigger_kind > EVG_TRIGGER_NORM_DIFF) return fail(EVG_ERR_INVALID, "unknown trigger_kind %u", cfg->trigger_kind);
   if (cfg->delivery_delay > 1) return fail(EVG_ERR_INVALID, "delivery_delay must be 0 or 1");
+  if (cfg->xhat_reset > 1) return fail(EVG_ERR_INVALID, "xhat_reset must be 0 or 1");
+  if (cfg->xhat_reset && cfg->delivery_delay)
+    return fail(EVG_ERR_INVALID, "xhat_reset = 1 is not available with delivery_delay = 1");
   if (cfg->access_mode > EVG_ACCESS_CACHED) return fail(EVG_ERR_INVALID, "unknown access_mode %u", cfg->access_mode);
   const uint32_t ce = cfg->chunk_elems ? cfg->chunk_elems : 8192u;
   if (ce != 1024 && ce != 2048 && ce != 4096 && ce != 8192)
@@ -442,6 +445,7 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   a.delay = g.delivery_delay;
   a.hist_fused = (g.topk_ppm && g.norm_mode == EVG_NORM_FUSED) ? 1u : 0u;
   a.cached = c->cached ? 1u : 0u;
+  a.xhat_reset = (g.xhat_reset && g.topk_ppm) ? 1u : 0u;
   const bool norm_diff = g.trigger_kind == EVG_TRIGGER_NORM_DIFF;
   // fused + whole-tensor sends: xhat's norm is a scalar per tensor and xhat is never read
   a.norm_src = !norm_diff ? 0u : (g.norm_mode == EVG_NORM_FUSED && !g.topk_ppm) ? 1u : 2u;
@@ -623,7 +627,7 @@ StateHeader state_header(evg_ctx* c) {
   h.trigger_kind = c->cfg.trigger_kind;
   h.norm_mode = c->cfg.norm_mode;
   h.thr_mode = c->cfg.thr_mode;
-  h.pad = c->cfg.delivery_delay;
+  h.pad = c->cfg.delivery_delay | (c->cfg.xhat_reset << 8);
   h.Npad = c->t.Npad;
   h.iters = c->iters;
   h.last_iter = c->last_iter;

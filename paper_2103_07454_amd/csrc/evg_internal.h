@@ -77,6 +77,7 @@ struct StepArgs {
                            // and squared xhat in partials / partials_hat
   uint32_t delay;          // messages of this iteration land after its updates
   uint32_t hist_fused;     // the update pass of the previous iteration already built pass A's histograms
+  uint32_t xhat_reset;     // a Top-K event resets the whole tensor's xhat to x
   uint32_t cached;         // the arenas fit the last-level cache: ordinary instead of streaming accesses
   uint32_t key0, key1;
   double decay_pow;        // decay^k

@@ -150,7 +150,10 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   const ChunkDesc cd = T.chunks[c];
   const uint32_t seg = r * T.L + cd.layer;
   const bool vl = T.valid_l[seg] != 0, vr = T.valid_r[seg] != 0;
-  const bool sent_whole = T.fired[seg] == 1;
+  // xhat := x for the whole tensor: after a whole send, or after any event when a Top-K
+  // event is read as resetting the tensor's xhat
+  const uint32_t my_event = T.fired[seg];
+  const bool sent_whole = my_event == 1 || (TOPK && A.xhat_reset && my_event == 2);
   const size_t base = (size_t)r * T.Npad + cd.off;
   const float third = 0.333333343f;   // (float)(1/3): the ring's mixing weight
   uint32_t e[SPW];
@@ -190,9 +193,11 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
       // hold) and the two messages that arrive in my mailboxes
       const uint32_t left = (r + T.P - 1) % T.P, right = (r + 1) % T.P;
       const uint32_t moff = T.layers[cd.layer].msg_off, j_lo = cd.j0 + sub0 * kSweep;
-      const Slice s0 = message_slice<SPW>(T, r, cd.layer, c, sub0, moff);
+      const Slice s0m = message_slice<SPW>(T, r, cd.layer, c, sub0, moff);
       Slice s1 = message_slice<SPW>(T, left, cd.layer, c, sub0, moff);
       Slice s2 = message_slice<SPW>(T, right, cd.layer, c, sub0, moff);
+      Slice s0 = s0m;
+      if (sent_whole) s0.n = 0;              // xhat has just been written from registers
       if (A.delay) { s1.n = 0; s2.n = 0; }   // the neighbours' messages land after this pass
       if (s0.n | s1.n | s2.n) {          // uniform
         for (uint32_t q = threadIdx.x; q < 3 * kWinWords; q += kThreads) pm[q] = 0;

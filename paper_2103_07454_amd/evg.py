@@ -51,7 +51,7 @@ class Config(C.Structure):
                 ("hist_len", C.c_uint32), ("delta_init", C.c_float), ("force_first", C.c_uint32),
                 ("topk_ppm", C.c_uint32), ("topk_key", C.c_uint32), ("grad_mode", C.c_uint32),
                 ("norm_mode", C.c_uint32), ("chunk_elems", C.c_uint32), ("trigger_kind", C.c_uint32),
-                ("delivery_delay", C.c_uint32), ("access_mode", C.c_uint32),
+                ("delivery_delay", C.c_uint32), ("xhat_reset", C.c_uint32), ("access_mode", C.c_uint32),
                 ("synth", Synth),
                 ("x", C.c_void_p), ("xhat", C.c_void_p), ("mbox_l", C.c_void_p),
                 ("mbox_r", C.c_void_p), ("vel", C.c_void_p)]
@@ -161,7 +161,7 @@ class Ring:
     def __init__(self, x0, layer_numel, layer_fan_in=None, *, lr=0.05, momentum=0.9,
                  thr_mode=THR_ADAPTIVE, thr_fixed=0.0, horizon=1.0, hist_len=1, delta_init=0.0,
                  force_first=1, topk_ppm=0, topk_key=KEY_ABS_DRIFT, grad_mode=GRAD_SYNTH,
-                 norm_mode=NORM_FUSED, chunk_elems=0, trigger_kind=TRIGGER_DRIFT_NORM, delivery_delay=0, access_mode=0, seed=0, dist=DIST_NORMAL, fan_in_scaling=0,
+                 norm_mode=NORM_FUSED, chunk_elems=0, trigger_kind=TRIGGER_DRIFT_NORM, delivery_delay=0, xhat_reset=0, access_mode=0, seed=0, dist=DIST_NORMAL, fan_in_scaling=0,
                  sigma0=0.0, decay=1.0, spike_prob=0.0, spike_gain=1.0, device="cuda:0",
                  mailbox_fill=None, stream=None):
         import torch
@@ -206,6 +206,7 @@ class Ring:
             cfg.norm_mode, cfg.chunk_elems, cfg.trigger_kind = norm_mode, chunk_elems, trigger_kind
             cfg.delivery_delay = delivery_delay
             cfg.access_mode = access_mode
+            cfg.xhat_reset = xhat_reset
             cfg.synth = Synth(seed, dist, fan_in_scaling, sigma0, decay, spike_prob, spike_gain)
             cfg.x, cfg.xhat = self.x.data_ptr(), self.xhat.data_ptr()
             cfg.mbox_l, cfg.mbox_r, cfg.vel = self.mbox_l.data_ptr(), self.mbox_r.data_ptr(), self.vel.data_ptr()

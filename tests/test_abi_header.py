@@ -42,7 +42,7 @@ extern "C" {
 struct orc_config { uint32_t P, L; const uint64_t* layer_numel; const uint32_t* layer_fan_in; float lr, momentum;
   uint32_t thr_mode; float thr_fixed; float horizon; uint32_t hist_len; float delta_init; uint32_t force_first;
   uint32_t topk_ppm, topk_key, trigger_kind, grad_mode; uint64_t seed; uint32_t dist, fan_in_scaling;
-  double sigma0, decay; float spike_prob, spike_gain; uint32_t delivery_delay; };
+  double sigma0, decay; float spike_prob, spike_gain; uint32_t delivery_delay, xhat_reset; };
 void* orc_create(const orc_config*, const float*);
 int orc_step(void*, uint64_t, const float*, const int8_t*);
 void orc_totals(void*, uint64_t*);
@@ -53,12 +53,12 @@ int main() {
   const uint32_t fan[4] = {16, 16, 8, 8};
   uint64_t N = 0; for (uint64_t n : numel) N += n;
   uint64_t events = 0;
-  for (int mode = 0; mode < 6; ++mode) {
+  for (int mode = 0; mode < 7; ++mode) {
     orc_config c{};
     c.P = 4; c.L = 4; c.layer_numel = numel; c.layer_fan_in = fan; c.lr = 0.05f; c.momentum = 0.9f;
     c.thr_mode = 1; c.horizon = 1.0f; c.hist_len = mode == 1 ? 3 : 1; c.force_first = 1;
     c.topk_ppm = mode >= 2 ? 100000 : 0; c.topk_key = mode == 3; c.trigger_kind = mode == 4;
-    c.delivery_delay = mode == 5; c.seed = 99; c.dist = mode == 2; c.fan_in_scaling = 1;
+    c.delivery_delay = mode == 5; c.xhat_reset = mode == 6; c.seed = 99; c.dist = mode == 2; c.fan_in_scaling = 1;
     c.sigma0 = 0.05; c.decay = 0.98; c.spike_prob = 0.2f; c.spike_gain = 5.0f;
     std::vector<float> x0(c.P * N, 0.25f);
     void* h = orc_create(&c, x0.data());

@@ -71,6 +71,8 @@ def base_cfg(evg, keep):
     (lambda c: setattr(c, "trigger_kind", 2), 1),
     (lambda c: setattr(c, "delivery_delay", 2), 1),
     (lambda c: setattr(c, "access_mode", 3), 1),
+    (lambda c: setattr(c, "xhat_reset", 2), 1),
+    (lambda c: (setattr(c, "xhat_reset", 1), setattr(c, "delivery_delay", 1)), 1),
     (lambda c: setattr(c, "chunk_elems", 1000), 1),
     (lambda c: setattr(c.synth, "decay", 0.0), 1),
     (lambda c: setattr(c.synth, "sigma0", -1.0), 1),

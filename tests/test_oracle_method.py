@@ -393,6 +393,63 @@ def test_topk_everything_equals_full_send(oracle_mod):
         assert np.array_equal(a.state(name), b.state(name))
 
 
+def test_xhat_reset_reading_of_a_topk_event(oracle_mod):
+    """xhat_reset = 1: a Top-K event resets the whole tensor's xhat to x (Section 4's
+    per-tensor xhat), while the neighbours' copies change only at the sent indices.
+    Checked against the states observed before each step: winners by brute force on
+    |x - xhat|, xhat == x for the whole tensor, untouched mailbox entries keep their values."""
+    w = small_workload(topk_ppm=200_000)
+    o = oracle_mod.Oracle.from_workload(w, xhat_reset=1)
+    ref = oracle_mod.Oracle.from_workload(w)              # default reading, same inputs
+    numel = w.layer_numel.astype(np.int64)
+    off = np.concatenate([[0], np.cumsum(numel)])
+    P, L = w.P, w.L
+    seen_topk = differs = 0
+    for k in range(30):
+        x_prev, xhat_prev = o.state("x"), o.state("xhat")
+        ml_prev, mr_prev = o.state("mbox_l"), o.state("mbox_r")
+        o.step(k)
+        ref.step(k)
+        d = o.decisions()
+        xhat, ml, mr = o.state("xhat"), o.state("mbox_l"), o.state("mbox_r")
+        for r in range(P):
+            for l in range(L):
+                sl = slice(off[l], off[l + 1])
+                if d["fired"][r, l] == 0:
+                    assert np.array_equal(xhat[r, sl], xhat_prev[r, sl])
+                    continue
+                assert np.array_equal(xhat[r, sl], x_prev[r, sl])           # whole tensor, either kind of event
+                if d["fired"][r, l] != 2:
+                    continue
+                seen_topk += 1
+                idx, val = o.message(r, l)
+                keys = np.abs(x_prev[r, sl] - xhat_prev[r, sl]).astype(np.float32).view(np.uint32)
+                K = oracle_mod.topk_count(numel[l], w.topk_ppm)
+                assert np.array_equal(idx, brute_topk(keys, K))
+                assert np.array_equal(val, x_prev[r, sl][idx])
+                for box, box_prev, nb in ((ml, ml_prev, (r + 1) % P), (mr, mr_prev, (r - 1) % P)):
+                    want = box_prev[nb, sl].copy()
+                    want[idx] = val
+                    assert np.array_equal(box[nb, sl], want, equal_nan=True)
+    assert seen_topk > 50
+    # the reading matters: the two runs part ways (under the default one unsent drift carries over)
+    assert not np.array_equal(o.state("xhat"), ref.state("xhat"))
+    assert not np.array_equal(o.state("x"), ref.state("x"))
+    t = o.totals()
+    assert t["index_words"] > 0 and t["bytes_sent"] == 8 * (t["value_words"] + t["index_words"])
+
+
+def test_xhat_reset_with_everything_sent_is_the_whole_send(oracle_mod):
+    w = small_workload()
+    a = oracle_mod.Oracle.from_workload(w)
+    b = oracle_mod.Oracle.from_workload(w, topk_ppm=1_000_000, xhat_reset=1)
+    for k in range(25):
+        a.step(k)
+        b.step(k)
+    for name in ("x", "xhat", "mbox_l", "mbox_r", "vel"):
+        assert np.array_equal(a.state(name), b.state(name))
+
+
 # --------------------------------------------------------------------------
 # determinism, overrides, final average
 # --------------------------------------------------------------------------
