@@ -179,6 +179,13 @@ def main():
                            "avg_launch_ms": avg_ms, "launches": n_upd,
                            "algorithmic_bytes_per_launch": upd_bytes}
         out["phase_ms_per_step"] = {p: ms / max(1, args.steps) for p, (ms, n) in phases.items()}
+        # the other HBM-bound phases against the same peak, on their share of the lower-bound bytes:
+        # whole sends move 12 B per fired element here (xhat := x rides in the update pass), the
+        # Top-K selection one key pass over x and xhat (8 B), packing writes the 8 rho message
+        alg = {"send_full": 12 * f_full, "topk_select": 8 * f_topk, "topk_send": 8 * rho * f_topk}
+        out["phase_frac_of_hbm_peak"] = {
+            p: b * elems / (phases[p][0] / max(1, args.steps) * 1e-3) / 1e9 / HBM_PEAK_GBS
+            for p, b in alg.items() if phases[p][0] > 0 and b > 0}
     if per_step:
         # iterations 0 and 1 fire every tensor (forced first event, then a zero threshold)
         ms = np.array([marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps)])
