@@ -69,6 +69,11 @@ def main():
                          "1 = difference of the norms")
     ap.add_argument("--delivery-delay", type=int, default=0,
                     help="1 = messages land after the iteration's updates (not a benchmark configuration)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of captured evg_step_next calls instead of K evg_step calls "
+                         "(same iterations; for the launch-bound small rings)")
+    ap.add_argument("--graph-steps", type=int, default=1,
+                    help="iterations recorded into the one graph (must divide --steps)")
     ap.add_argument("--xhat-reset", type=int, default=0,
                     help="1 = a Top-K event resets the whole tensor's xhat (not a benchmark configuration)")
     ap.add_argument("--diag-grad-buffer", action="store_true",
@@ -89,7 +94,14 @@ def main():
 
     gbuf = None
 
+    side = torch.cuda.Stream() if args.graph else None
+
     def make():
+        if side is not None:
+            with torch.cuda.stream(side):
+                return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk, trigger_kind=args.trigger_kind,
+                                              delivery_delay=args.delivery_delay, xhat_reset=args.xhat_reset,
+                                              stream=side)
         if args.diag_grad_buffer:
             return evg.Ring.from_workload(w, x0, chunk_elems=args.chunk, grad_mode=evg.GRAD_BUFFER,
                                           trigger_kind=args.trigger_kind, delivery_delay=args.delivery_delay,
@@ -109,12 +121,26 @@ def main():
 
     # timed region: fresh state, iterations 0..K-1, no instrumentation of any kind
     ring = make()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        ring.step(k, gbuf)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        assert args.steps % args.graph_steps == 0
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(args.graph_steps):
+                ring.step_next()               # recorded, not run: the replays are iterations 0..K-1
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps // args.graph_steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        assert ring.stats()["iters"] == args.steps
+    else:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            ring.step(k, gbuf)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
 
     # the same K iterations once more from a fresh state, now with the library's phase
     # timers and one event per step (these cost a few microseconds per step, which is
@@ -157,6 +183,7 @@ def main():
                    + ("+XHAT_RESET" if args.xhat_reset else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
                    "threshold": "adaptive" if w.thr_mode else "fixed", "topk_ppm": w.topk_ppm,
                    "chunk_elems": args.chunk or 8192,
+                   "launch": f"replays of one captured HIP graph of {args.graph_steps} iteration(s)" if args.graph else "one evg_step call per iteration",
                    "fraction_fired_full": f_full, "fraction_fired_topk": f_topk,
                    "messages_pct_of_regular": 100.0 * st["events_total"] / max(1, st["regular_events"]),
                    "communication_pct_of_regular":

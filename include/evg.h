@@ -185,8 +185,21 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream);
  * grad: DEVICE array laid out like x, required iff grad_mode == EVG_GRAD_BUFFER,
  * read during the step.  Asynchronous on the context's stream.  The iteration number
  * and what depends on it travel as kernel arguments, so a captured HIP graph of this
- * call must not be replayed for another iteration. */
+ * call must not be replayed for another iteration (evg_step_next is the call for that). */
 evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad);
+
+/* The same iteration as evg_step, for the iteration that follows the context's last one
+ * (0 after evg_init), with the iteration number and what depends on it kept in device
+ * memory: nothing in the launch sequence changes from call to call, so a HIP graph captured
+ * around one call (hipStreamBeginCapture on the context's stream) may be replayed, each
+ * replay being the next iteration.  For callers that drive the iterations from a graph.
+ * Makes no synchronising or allocating call, records no memset and no event (the phase
+ * timers of evg_timing skip these steps).  Iterations up to 65535; the first call that
+ * needs the host's view of the iteration again (evg_step, evg_stats, evg_state_export)
+ * synchronises and reports EVG_ERR_STATE if that limit was passed; once this call has been
+ * used on a context, every evg_step on it synchronises first, to learn how far replays have
+ * gone.  grad as in evg_step: a captured graph keeps reading the same pointer. */
+evg_status evg_step_next(evg_ctx* c, const float* grad);
 
 /* Waits for the stream, then fills *out (array members that are non-NULL too). */
 evg_status evg_stats(evg_ctx* c, evg_stats_t* out);

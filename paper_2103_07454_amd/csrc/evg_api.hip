@@ -41,6 +41,8 @@ inline uint64_t pad_to(uint64_t v, uint64_t m) { return (v + m - 1) / m * m; }
 
 struct TimerPair { hipEvent_t a, b; int phase; };
 
+constexpr uint32_t kDecayTable = 1u << 16;   // iterations a replayable step can reach
+
 }  // namespace
 
 struct evg_ctx {
@@ -58,6 +60,9 @@ struct evg_ctx {
   int64_t last_iter = -1;
   bool messages_live = false;       // the message buffers hold the last step's messages
   bool cached = false;              // the five arenas together fit the last-level cache
+  bool device_ahead = false;        // evg_step_next has been used: replays of a captured graph
+                                    // advance the device's iteration without the host seeing
+                                    // it, so iters / last_iter are re-read whenever needed
   // timing
   bool timing = false;
   std::vector<TimerPair> pending;
@@ -388,6 +393,17 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   TRY_OR_FREE(c->dalloc(&t.seg_woff_full, S, true));
   TRY_OR_FREE(c->dalloc(&t.seg_woff_topk, S, true));
   TRY_OR_FREE(c->dalloc(&t.counts, 4, true));
+  TRY_OR_FREE(c->dalloc(&t.it, 1, true));
+  {
+    // decay^k as evg_step computes it, for the steps that take k from the device
+    std::vector<double> tab(kDecayTable);
+    for (uint32_t k = 0; k < kDecayTable; ++k) tab[k] = std::pow(cfg->synth.decay, (double)k);
+    double* d_tab = nullptr;
+    TRY_OR_FREE(c->dalloc(&d_tab, kDecayTable, false));
+    HIP_OR_FREE(hipMemcpy(d_tab, tab.data(), kDecayTable * sizeof(double), hipMemcpyHostToDevice));
+    t.decay_tab = d_tab;
+    t.decay_len = kDecayTable;
+  }
   TRY_OR_FREE(c->dalloc(&t.work_full, P * C, true));
   if (cfg->topk_ppm) {
     TRY_OR_FREE(c->dalloc(&t.work_topk, P * C, true));
@@ -421,47 +437,30 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   return EVG_OK;
 }
 
-evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
-  if (!c) return fail(EVG_ERR_INVALID, "context is NULL");
-  if ((int64_t)iter <= c->last_iter || iter >= 0x7FFFFFFFull)
-    return fail(EVG_ERR_STATE, "iteration %llu does not follow %lld", (unsigned long long)iter,
-                (long long)c->last_iter);
+// Brings iters / last_iter up to date with the device after replayable steps.
+static evg_status refresh_iteration(evg_ctx* c) {
+  if (!c->device_ahead) return EVG_OK;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  IterState it{};
+  HIP_TRY(hipMemcpy(&it, c->t.it, sizeof it, hipMemcpyDeviceToHost));
+  if (it.overflow)
+    return fail(EVG_ERR_STATE, "evg_step_next ran past iteration %u, the end of its decay table", kDecayTable - 1);
+  c->iters = it.iters;
+  c->last_iter = (int64_t)it.k_next - 1;
+  return EVG_OK;
+}
+
+// The launch sequence of one iteration.  `timed`: bracket the phases with events.
+static evg_status enqueue_step(evg_ctx* c, const StepArgs& a, bool timed) {
   const evg_config& g = c->cfg;
-  if (g.grad_mode == EVG_GRAD_BUFFER) {
-    if (!grad) return fail(EVG_ERR_INVALID, "grad_mode is EVG_GRAD_BUFFER but grad is NULL");
-    if ((uintptr_t)grad % 16) return fail(EVG_ERR_ALIGN, "grad is not 16-byte aligned");
-    evg_status gs = check_device_array(grad, (uint64_t)c->t.P * c->t.Npad * 4, "grad");
-    if (gs != EVG_OK) return gs;
-  }
-  StepArgs a{};
-  a.k = (uint32_t)iter;
-  a.lr = g.lr;
-  a.mu = g.momentum;
-  a.thr_mode = g.thr_mode;
-  a.horizon = g.horizon;
-  a.force_first = g.force_first ? 1u : 0u;
-  a.topk_on = g.topk_ppm ? 1u : 0u;
-  a.topk_key = g.topk_key;
-  a.delay = g.delivery_delay;
-  a.hist_fused = (g.topk_ppm && g.norm_mode == EVG_NORM_FUSED) ? 1u : 0u;
-  a.cached = c->cached ? 1u : 0u;
-  a.xhat_reset = (g.xhat_reset && g.topk_ppm) ? 1u : 0u;
-  const bool norm_diff = g.trigger_kind == EVG_TRIGGER_NORM_DIFF;
-  // fused + whole-tensor sends: xhat's norm is a scalar per tensor and xhat is never read
-  a.norm_src = !norm_diff ? 0u : (g.norm_mode == EVG_NORM_FUSED && !g.topk_ppm) ? 1u : 2u;
-  a.key0 = (uint32_t)g.synth.seed;
-  a.key1 = (uint32_t)(g.synth.seed >> 32);
-  a.decay_pow = std::pow(g.synth.decay, (double)iter);
-  a.spike_prob = g.synth.spike_prob;
-  a.spike_gain = g.synth.spike_gain;
-  a.grad = grad;
   const Tables& t = c->t;
   const bool fused = g.norm_mode == EVG_NORM_FUSED;
-  if (c->timing && c->pending.size() > 4096) {
-    evg_status st = c->drain_timers();
-    if (st != EVG_OK) return st;
-  }
+  const bool norm_diff = g.trigger_kind == EVG_TRIGGER_NORM_DIFF;
+  const bool was_timing = c->timing;
+  c->timing = was_timing && timed;
+  struct Restore { evg_ctx* c; bool v; ~Restore() { c->timing = v; } } restore{c, was_timing};
   evg_status st;
+  if (a.from_device) HIP_TRY(launch_begin(t, c->stream));
   if (!fused) {
     Phase ph(c, EVG_PH_NORM);
     HIP_TRY(launch_norm(t, norm_diff, c->stream));
@@ -470,7 +469,7 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
   {
     Phase ph(c, EVG_PH_TRIGGER);
     HIP_TRY(launch_trigger(t, a, c->stream));
-    HIP_TRY(launch_scan(t, c->stream));
+    HIP_TRY(launch_scan(t, a, c->stream));
     HIP_TRY(launch_expand(t, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
   }
@@ -502,9 +501,69 @@ evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
     HIP_TRY(launch_deliver(t, c->chunk_elems, c->work_grid, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
   }
+  c->messages_live = true;
+  return EVG_OK;
+}
+
+// Everything of StepArgs that does not depend on the iteration.
+static evg_status fixed_args(evg_ctx* c, const float* grad, StepArgs* out) {
+  const evg_config& g = c->cfg;
+  if (g.grad_mode == EVG_GRAD_BUFFER) {
+    if (!grad) return fail(EVG_ERR_INVALID, "grad_mode is EVG_GRAD_BUFFER but grad is NULL");
+    if ((uintptr_t)grad % 16) return fail(EVG_ERR_ALIGN, "grad is not 16-byte aligned");
+    evg_status gs = check_device_array(grad, (uint64_t)c->t.P * c->t.Npad * 4, "grad");
+    if (gs != EVG_OK) return gs;
+  }
+  StepArgs a{};
+  a.lr = g.lr;
+  a.mu = g.momentum;
+  a.thr_mode = g.thr_mode;
+  a.horizon = g.horizon;
+  a.force_first = g.force_first ? 1u : 0u;
+  a.topk_on = g.topk_ppm ? 1u : 0u;
+  a.topk_key = g.topk_key;
+  a.delay = g.delivery_delay;
+  a.hist_fused = (g.topk_ppm && g.norm_mode == EVG_NORM_FUSED) ? 1u : 0u;
+  a.cached = c->cached ? 1u : 0u;
+  a.xhat_reset = (g.xhat_reset && g.topk_ppm) ? 1u : 0u;
+  const bool norm_diff = g.trigger_kind == EVG_TRIGGER_NORM_DIFF;
+  // fused + whole-tensor sends: xhat's norm is a scalar per tensor and xhat is never read
+  a.norm_src = !norm_diff ? 0u : (g.norm_mode == EVG_NORM_FUSED && !g.topk_ppm) ? 1u : 2u;
+  a.key0 = (uint32_t)g.synth.seed;
+  a.key1 = (uint32_t)(g.synth.seed >> 32);
+  a.spike_prob = g.synth.spike_prob;
+  a.spike_gain = g.synth.spike_gain;
+  a.grad = grad;
+  *out = a;
+  return EVG_OK;
+}
+
+evg_status evg_step(evg_ctx* c, uint64_t iter, const float* grad) {
+  if (!c) return fail(EVG_ERR_INVALID, "context is NULL");
+  evg_status st = refresh_iteration(c);
+  if (st != EVG_OK) return st;
+  if ((int64_t)iter <= c->last_iter || iter >= 0x7FFFFFFFull)
+    return fail(EVG_ERR_STATE, "iteration %llu does not follow %lld", (unsigned long long)iter,
+                (long long)c->last_iter);
+  StepArgs a{};
+  if ((st = fixed_args(c, grad, &a)) != EVG_OK) return st;
+  a.k = (uint32_t)iter;
+  a.decay_pow = std::pow(c->cfg.synth.decay, (double)iter);
+  if (c->timing && c->pending.size() > 4096 && (st = c->drain_timers()) != EVG_OK) return st;
+  if ((st = enqueue_step(c, a, true)) != EVG_OK) return st;
   c->last_iter = (int64_t)iter;
   c->iters += 1;
-  c->messages_live = true;
+  return EVG_OK;
+}
+
+evg_status evg_step_next(evg_ctx* c, const float* grad) {
+  if (!c) return fail(EVG_ERR_INVALID, "context is NULL");
+  StepArgs a{};
+  evg_status st = fixed_args(c, grad, &a);
+  if (st != EVG_OK) return st;
+  a.from_device = 1;
+  if ((st = enqueue_step(c, a, false)) != EVG_OK) return st;
+  c->device_ahead = true;
   return EVG_OK;
 }
 
@@ -513,6 +572,8 @@ evg_status evg_stats(evg_ctx* c, evg_stats_t* out) {
   const Tables& t = c->t;
   const size_t S = t.S;
   HIP_TRY(hipStreamSynchronize(c->stream));
+  evg_status rs = refresh_iteration(c);
+  if (rs != EVG_OK) return rs;
   std::vector<uint32_t> ef(S), et(S), nt(S), nf(S);
   HIP_TRY(hipMemcpy(ef.data(), t.ev_full, S * 4, hipMemcpyDeviceToHost));
   HIP_TRY(hipMemcpy(et.data(), t.ev_topk, S * 4, hipMemcpyDeviceToHost));
@@ -611,7 +672,8 @@ std::vector<Piece> state_pieces(evg_ctx* c) {
       {t.delta, S * 4}, {t.last_norm, S * 4}, {t.delta_before, S * 4}, {t.last_event, S * 4},
       {t.valid_l, S}, {t.valid_r, S}, {t.fired, S}, {t.near_tie, S},
       {t.ev_full, S * 4}, {t.ev_topk, S * 4}, {t.near_cnt, S * 4}, {t.nonfinite_cnt, S * 4},
-      {t.slope_hist, S * t.hist_len * 4}, {t.slope_cnt, S * 4}, {t.partials, sweeps * 8}};
+      {t.slope_hist, S * t.hist_len * 4}, {t.slope_cnt, S * 4}, {t.partials, sweeps * 8},
+      {t.it, sizeof(IterState)}};
   if (t.partials_hat) { v.push_back({t.partials_hat, sweeps * 8}); v.push_back({t.xhat_sq, S * 8}); }
   if (t.hist) v.push_back({t.hist, S * kHistBins * 4});
   return v;
@@ -620,7 +682,7 @@ std::vector<Piece> state_pieces(evg_ctx* c) {
 StateHeader state_header(evg_ctx* c) {
   StateHeader h{};
   std::memcpy(h.magic, "EVGSTATE", 8);
-  h.version = 1;
+  h.version = 2;
   h.P = c->t.P; h.L = c->t.L; h.C = c->t.C; h.SW = c->t.SW; h.S = c->t.S;
   h.hist_len = c->t.hist_len;
   h.topk_ppm = c->cfg.topk_ppm;
@@ -651,6 +713,8 @@ evg_status evg_state_export(evg_ctx* c, void* blob, uint64_t capacity) {
     return fail(EVG_ERR_INVALID, "blob holds %llu bytes, %llu needed", (unsigned long long)capacity,
                 (unsigned long long)evg_state_size(c));
   HIP_TRY(hipStreamSynchronize(c->stream));
+  evg_status rs = refresh_iteration(c);
+  if (rs != EVG_OK) return rs;
   const StateHeader h = state_header(c);
   char* out = static_cast<char*>(blob);
   std::memcpy(out, &h, sizeof h);

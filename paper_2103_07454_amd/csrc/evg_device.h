@@ -8,6 +8,14 @@ namespace evg {
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
 __device__ __forceinline__ uint32_t wave_id() { return threadIdx.x >> 6; }
 
+// The iteration number and decay^k of the step in flight (uniform loads).
+__device__ __forceinline__ uint32_t step_k(const Tables& T, const StepArgs& A) {
+  return A.from_device ? T.it->k : A.k;
+}
+__device__ __forceinline__ double step_decay(const Tables& T, const StepArgs& A) {
+  return A.from_device ? T.it->decay_pow : A.decay_pow;
+}
+
 // Streaming (non-temporal) 16-byte accesses: every arena is far larger than the
 // caches and is touched once per pass, so lines are not worth keeping.
 typedef float f32x4 __attribute__((ext_vector_type(4)));

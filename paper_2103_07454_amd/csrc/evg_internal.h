@@ -29,6 +29,17 @@ struct LayerDesc {
   double sig_base;   // sigma0 [/ sqrt(fan_in)]
 };
 
+// The iteration as the device knows it.  evg_step passes the iteration by value; a step
+// that must be replayable from a captured graph (evg_step_next) reads it from here instead.
+struct IterState {
+  uint32_t k;          // iteration of the step in flight (set by k_begin in replayable steps)
+  uint32_t k_next;     // the iteration after the last completed step
+  uint64_t iters;      // steps completed
+  double decay_pow;    // decay^k for the step in flight (replayable steps)
+  uint32_t overflow;   // a replayable step ran past the decay table
+  uint32_t pad;
+};
+
 // Device pointers and sizes, passed to kernels by value.
 struct Tables {
   const ChunkDesc* chunks;
@@ -57,6 +68,9 @@ struct Tables {
   uint32_t* chunk_sub;     // [P*C*(SW+1)] winners before each 1024-element sweep of a chunk,
                            // as message slots (entry 0 = the chunk's first slot)
   uint32_t* msg_idx; float* msg_val;          // [P*Ktot]
+  IterState* it;
+  const double* decay_tab;   // decay^k for k < decay_len (replayable steps only)
+  uint32_t decay_len;
   uint32_t P, L, C, S;
   uint32_t SW;             // 1024-element sweeps per chunk
   uint32_t hist_len;
@@ -77,6 +91,7 @@ struct StepArgs {
                            // and squared xhat in partials / partials_hat
   uint32_t delay;          // messages of this iteration land after its updates
   uint32_t hist_fused;     // the update pass of the previous iteration already built pass A's histograms
+  uint32_t from_device;    // take k and decay^k from IterState instead of the two fields here
   uint32_t xhat_reset;     // a Top-K event resets the whole tensor's xhat to x
   uint32_t cached;         // the arenas fit the last-level cache: ordinary instead of streaming accesses
   uint32_t key0, key1;
@@ -91,7 +106,8 @@ hipError_t launch_norm(const Tables& t, bool norm_diff, hipStream_t s);
 hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t dist, uint32_t grad_mode,
                          int norm, hipStream_t s);
 hipError_t launch_trigger(const Tables& t, const StepArgs& a, hipStream_t s);
-hipError_t launch_scan(const Tables& t, hipStream_t s);
+hipError_t launch_begin(const Tables& t, hipStream_t s);
+hipError_t launch_scan(const Tables& t, const StepArgs& a, hipStream_t s);
 hipError_t launch_expand(const Tables& t, hipStream_t s);
 hipError_t launch_copy(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid, hipStream_t s);
 hipError_t launch_deliver(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s);

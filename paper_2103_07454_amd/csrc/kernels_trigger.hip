@@ -31,6 +31,7 @@ __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
   }
   if (lane_id() != 0) return;
 
+  const uint32_t k = step_k(T, A);
   float d;
   if (A.norm_src == 0) {
     d = (float)sqrt(acc);
@@ -45,12 +46,12 @@ __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
   const bool near = __builtin_fabsf(d - dl) < 1e-6f * dl;
   T.near_tie[seg] = near ? 1 : 0;
   if (near) T.near_cnt[seg] += 1;
-  const bool fire = (A.force_first && A.k == 0) || (d >= dl);   // NaN never fires
+  const bool fire = (A.force_first && k == 0) || (d >= dl);   // NaN never fires
   uint8_t code = 0;
   if (fire) {
     const int32_t khat = T.last_event[seg];
     if (A.thr_mode == 1) {
-      const float slope = d / (float)((int32_t)A.k - khat);
+      const float slope = d / (float)((int32_t)k - khat);
       if (T.hist_len <= 1) {
         T.delta[seg] = A.horizon * slope;
       } else {
@@ -68,7 +69,7 @@ __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
         T.delta[seg] = A.horizon * (sum / (float)cnt);
       }
     }
-    T.last_event[seg] = (int32_t)A.k;
+    T.last_event[seg] = (int32_t)k;
     if (A.norm_src == 1) T.xhat_sq[seg] = acc;    // the whole tensor is sent: xhat becomes x
     // a tensor's first message has nothing to patch on the receiving side: send it whole
     if (!A.topk_on || khat < 0) { code = 1; T.ev_full[seg] += 1; }
@@ -82,8 +83,21 @@ __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
   T.fired[seg] = code;
 }
 
-// One workgroup of 1024 threads scans all P*L flags.
-__global__ __launch_bounds__(1024) void k_scan(Tables T) {
+// First kernel of a replayable step: one thread moves the device's iteration on.
+__global__ void k_begin(Tables T) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const uint32_t k = T.it->k_next;
+  T.it->k = k;
+  if (k >= T.decay_len) T.it->overflow = 1;
+  T.it->decay_pow = T.decay_tab[k < T.decay_len ? k : T.decay_len - 1];
+}
+
+// One workgroup of 1024 threads scans all P*L flags.  It runs once per step, after the
+// trigger tests: its first thread also closes the step's bookkeeping.
+// EXPAND: each thread also writes the chunk lists of its own tensors (small rings: one
+// dependent launch less; large rings leave that to k_expand's many wavefronts).
+template <bool EXPAND>
+__global__ __launch_bounds__(1024) void k_scan(Tables T, StepArgs A) {
   __shared__ uint32_t ws[16];
   const uint32_t per = (T.S + 1023u) / 1024u;
   const uint32_t lo = threadIdx.x * per;
@@ -102,10 +116,19 @@ __global__ __launch_bounds__(1024) void k_scan(Tables T) {
     const uint32_t f = T.fired[s], nc = T.layers[s % T.L].nchunks;
     T.seg_woff_full[s] = of;
     T.seg_woff_topk[s] = ot;
+    if (EXPAND && f) {
+      uint32_t* dst = f == 1 ? T.work_full + of : T.work_topk + ot;
+      const uint32_t first = (s / T.L) * T.C + T.layers[s % T.L].chunk0;
+      for (uint32_t i = 0; i < nc; ++i) dst[i] = first + i;
+    }
     if (f == 1) of += nc;
     if (f == 2) ot += nc;
   }
-  if (threadIdx.x == 0) { T.counts[0] = tf; T.counts[1] = tt; T.counts[2] = ts; }
+  if (threadIdx.x == 0) {
+    T.counts[0] = tf; T.counts[1] = tt; T.counts[2] = ts;
+    T.it->k_next = step_k(T, A) + 1;
+    T.it->iters += 1;
+  }
 }
 
 __global__ __launch_bounds__(kThreads) void k_expand(Tables T) {
@@ -150,12 +173,22 @@ hipError_t launch_trigger(const Tables& t, const StepArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_scan(const Tables& t, hipStream_t s) {
-  k_scan<<<dim3(1), dim3(1024), 0, s>>>(t);
+hipError_t launch_begin(const Tables& t, hipStream_t s) {
+  k_begin<<<dim3(1), dim3(64), 0, s>>>(t);
+  return hipGetLastError();
+}
+
+// Rings with at most this many chunks in all have their lists written by the scan itself.
+static bool scan_expands(const Tables& t) { return (uint64_t)t.P * t.C <= 8192; }
+
+hipError_t launch_scan(const Tables& t, const StepArgs& a, hipStream_t s) {
+  if (scan_expands(t)) k_scan<true><<<dim3(1), dim3(1024), 0, s>>>(t, a);
+  else k_scan<false><<<dim3(1), dim3(1024), 0, s>>>(t, a);
   return hipGetLastError();
 }
 
 hipError_t launch_expand(const Tables& t, hipStream_t s) {
+  if (scan_expands(t)) return hipSuccess;
   const uint32_t grid = (t.S + 3) / 4;
   k_expand<<<dim3(grid), dim3(kThreads), 0, s>>>(t);
   return hipGetLastError();

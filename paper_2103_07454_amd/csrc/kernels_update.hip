@@ -156,6 +156,7 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   const bool sent_whole = my_event == 1 || (TOPK && A.xhat_reset && my_event == 2);
   const size_t base = (size_t)r * T.Npad + cd.off;
   const float third = 0.333333343f;   // (float)(1/3): the ring's mixing weight
+  const uint32_t k_iter = step_k(T, A);
   uint32_t e[SPW];
   bool live[SPW];
 #pragma unroll
@@ -226,22 +227,22 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
     for (int u = 0; u < SPW; ++u) {
       if (live[u]) {
         if (!GRADBUF) {
-          const float sg = (float)(T.layers[cd.layer].sig_base * A.decay_pow);
+          const float sg = (float)(T.layers[cd.layer].sig_base * step_decay(T, A));
           if (DIST == 0) {
             float z[4];
-            normals4(philox((cd.j0 + e[u]) >> 2, cd.layer, A.k, r, A.key0, A.key1), z);
+            normals4(philox((cd.j0 + e[u]) >> 2, cd.layer, k_iter, r, A.key0, A.key1), z);
 #pragma unroll
             for (int i = 0; i < 4; ++i) g[u][i] = sg * z[i];
           } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               float z[4];
-              normals4(philox(cd.j0 + e[u] + i, cd.layer, A.k, r, A.key0, A.key1), z);
+              normals4(philox(cd.j0 + e[u] + i, cd.layer, k_iter, r, A.key0, A.key1), z);
               g[u][i] = sg * student_t3(z);
             }
           }
           if (A.spike_prob > 0.0f) {
-            const Rand4 sp = philox(0u, 0xFFFFFFFFu, A.k, r, A.key0, A.key1);
+            const Rand4 sp = philox(0u, 0xFFFFFFFFu, k_iter, r, A.key0, A.key1);
             if (unit_open(sp.w[0]) < A.spike_prob) {
 #pragma unroll
               for (int i = 0; i < 4; ++i) g[u][i] = g[u][i] * A.spike_gain;

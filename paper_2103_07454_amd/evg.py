@@ -25,7 +25,7 @@ ACCESS_AUTO, ACCESS_STREAM, ACCESS_CACHED = 0, 1, 2
 TRIGGER_DRIFT_NORM, TRIGGER_NORM_DIFF = 0, 1
 PHASES = ("norm", "trigger", "send_full", "topk_select", "topk_send", "update", "deliver")
 
-EXPORTS = ("evg_padded_numel", "evg_layer_offsets", "evg_init", "evg_step", "evg_stats",
+EXPORTS = ("evg_padded_numel", "evg_layer_offsets", "evg_init", "evg_step", "evg_step_next", "evg_stats",
            "evg_last_decisions", "evg_message", "evg_average", "evg_state_size", "evg_state_export",
            "evg_state_import", "evg_timing", "evg_timing_read",
            "evg_destroy", "evg_strerror", "evg_error_text")
@@ -87,6 +87,7 @@ def lib():
         l.evg_layer_offsets.argtypes = [C.c_uint32, u64p, u64p]
         l.evg_init.argtypes = [C.POINTER(vp), C.POINTER(Config), vp]
         l.evg_step.argtypes = [vp, C.c_uint64, vp]
+        l.evg_step_next.argtypes = [vp, vp]
         l.evg_stats.argtypes = [vp, C.POINTER(Stats)]
         l.evg_last_decisions.argtypes = [vp, vp, vp, vp, vp]
         l.evg_message.argtypes = [vp, C.c_uint32, C.c_uint32, vp, vp, C.c_uint64, u64p]
@@ -236,6 +237,13 @@ class Ring:
         if grad is not None:
             g = C.c_void_p(grad.data_ptr())
         _check(lib().evg_step(self._h, int(k), g))
+
+    def step_next(self, grad=None):
+        """Enqueue the iteration after the last one; replayable from a captured graph."""
+        g = None
+        if grad is not None:
+            g = C.c_void_p(grad.data_ptr())
+        _check(lib().evg_step_next(self._h, g))
 
     def stats(self, arrays=False):
         st = Stats()
