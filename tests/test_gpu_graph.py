@@ -62,30 +62,34 @@ def test_step_next_is_the_next_iteration(evg, topk):
     same(a, c)
 
 
-@pytest.mark.parametrize("topk", [0, 100_000])
-def test_captured_step_replays_as_successive_iterations(evg, topk):
+@pytest.mark.parametrize("topk,buffer", [(0, False), (100_000, False), (100_000, True)])
+def test_captured_step_replays_as_successive_iterations(evg, topk, buffer):
     import torch
     w = workload(topk_ppm=topk)
-    ref = evg.Ring.from_workload(w)
+    over = dict(grad_mode=evg.GRAD_BUFFER) if buffer else {}
+    ref = evg.Ring.from_workload(w, **over)
+    g = None
+    if buffer:       # the captured graph keeps reading this one array
+        g = torch.from_numpy(ref.layout.pad(inputs.random_grads(w.P, w.N, 8, 0.02))).cuda()
     s = torch.cuda.Stream()
     with torch.cuda.stream(s):
-        ring = evg.Ring.from_workload(w, stream=s)
-        ring.step_next()                      # iterations 0 and 1, eagerly
-        ring.step_next()
+        ring = evg.Ring.from_workload(w, stream=s, **over)
+        ring.step_next(g)                     # iterations 0 and 1, eagerly
+        ring.step_next(g)
     s.synchronize()
-    ref.step(0)
-    ref.step(1)
+    ref.step(0, g)
+    ref.step(1, g)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=s):
-        ring.step_next()                      # recorded, not run
+        ring.step_next(g)                     # recorded, not run
     same(ref, ring)                           # the capture itself changed nothing
     junk = torch.zeros(1 << 20, device="cuda")
     for k in range(2, 12):
         graph.replay()
-        ref.step(k)
+        ref.step(k, g)
         junk.add_(1.0)                        # eager work of the program's own between replays
         torch.cuda.synchronize()
         same(ref, ring)
     assert ring.stats()["iters"] == 12 and float(junk[0]) == 10.0
-    ring.step(12); ref.step(12)               # back to the eager call
+    ring.step(12, g); ref.step(12, g)         # back to the eager call
     same(ref, ring)
