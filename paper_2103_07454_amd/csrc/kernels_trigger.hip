@@ -11,9 +11,8 @@
 
 namespace evg {
 
-__global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
-  const uint32_t seg = blockIdx.x * (kThreads / 64) + wave_id();
-  if (seg >= T.S) return;           // whole wavefront leaves; no workgroup barrier below
+// The trigger test of one (worker, tensor), by one whole wavefront.
+__device__ __forceinline__ void trigger_segment(const Tables& T, const StepArgs& A, uint32_t seg) {
   const uint32_t r = seg / T.L, l = seg % T.L;
   const LayerDesc ld = T.layers[l];
   const double* part = T.partials + ((size_t)r * T.C + ld.chunk0) * T.SW;
@@ -83,6 +82,12 @@ __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
   T.fired[seg] = code;
 }
 
+__global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
+  const uint32_t seg = blockIdx.x * (kThreads / 64) + wave_id();
+  if (seg >= T.S) return;           // whole wavefront leaves; no workgroup barrier below
+  trigger_segment(T, A, seg);
+}
+
 // First kernel of a replayable step: one thread moves the device's iteration on.
 __global__ void k_begin(Tables T) {
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
@@ -97,8 +102,7 @@ __global__ void k_begin(Tables T) {
 // EXPAND: each thread also writes the chunk lists of its own tensors (small rings: one
 // dependent launch less; large rings leave that to k_expand's many wavefronts).
 template <bool EXPAND>
-__global__ __launch_bounds__(1024) void k_scan(Tables T, StepArgs A) {
-  __shared__ uint32_t ws[16];
+__device__ __forceinline__ void scan_segments(const Tables& T, const StepArgs& A, uint32_t* ws) {
   const uint32_t per = (T.S + 1023u) / 1024u;
   const uint32_t lo = threadIdx.x * per;
   const uint32_t hi = lo + per < T.S ? lo + per : T.S;
@@ -129,6 +133,21 @@ __global__ __launch_bounds__(1024) void k_scan(Tables T, StepArgs A) {
     T.it->k_next = step_k(T, A) + 1;
     T.it->iters += 1;
   }
+}
+
+template <bool EXPAND>
+__global__ __launch_bounds__(1024) void k_scan(Tables T, StepArgs A) {
+  __shared__ uint32_t ws[16];
+  scan_segments<EXPAND>(T, A, ws);
+}
+
+// Rings of a few tensors in all: the sixteen wavefronts of one workgroup run the trigger
+// tests, then the same workgroup scans and writes the lists -- one launch instead of two.
+__global__ __launch_bounds__(1024) void k_front(Tables T, StepArgs A) {
+  __shared__ uint32_t ws[16];
+  for (uint32_t seg = wave_id(); seg < T.S; seg += 16) trigger_segment(T, A, seg);
+  __syncthreads();                  // the flags written above are read below by other wavefronts
+  scan_segments<true>(T, A, ws);
 }
 
 __global__ __launch_bounds__(kThreads) void k_expand(Tables T) {
@@ -167,7 +186,16 @@ __global__ __launch_bounds__(kThreads) void k_copy(Tables T) {
   }
 }
 
+// Rings with at most this many chunks in all have their lists written by the scan itself.
+static bool scan_expands(const Tables& t) { return (uint64_t)t.P * t.C <= 8192; }
+// ... and those with at most 64 tensors in all run trigger, scan and lists as one workgroup.
+static bool one_front(const Tables& t) { return t.S <= 64 && scan_expands(t); }
+
 hipError_t launch_trigger(const Tables& t, const StepArgs& a, hipStream_t s) {
+  if (one_front(t)) {
+    k_front<<<dim3(1), dim3(1024), 0, s>>>(t, a);
+    return hipGetLastError();
+  }
   const uint32_t grid = (t.S + 3) / 4;
   k_trigger<<<dim3(grid), dim3(kThreads), 0, s>>>(t, a);
   return hipGetLastError();
@@ -178,10 +206,8 @@ hipError_t launch_begin(const Tables& t, hipStream_t s) {
   return hipGetLastError();
 }
 
-// Rings with at most this many chunks in all have their lists written by the scan itself.
-static bool scan_expands(const Tables& t) { return (uint64_t)t.P * t.C <= 8192; }
-
 hipError_t launch_scan(const Tables& t, const StepArgs& a, hipStream_t s) {
+  if (one_front(t)) return hipSuccess;
   if (scan_expands(t)) k_scan<true><<<dim3(1), dim3(1024), 0, s>>>(t, a);
   else k_scan<false><<<dim3(1), dim3(1024), 0, s>>>(t, a);
   return hipGetLastError();
