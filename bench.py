@@ -182,7 +182,8 @@ def main():
                    + ("+DELAYED_DELIVERY" if args.delivery_delay else "")
                    + ("+XHAT_RESET" if args.xhat_reset else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
                    "threshold": "adaptive" if w.thr_mode else "fixed", "topk_ppm": w.topk_ppm,
-                   "chunk_elems": args.chunk or 8192,
+                   "chunk_elems": args.chunk or (2048 if 5 * 4 * w.P * evg.padded_numel(w.layer_numel) <= (128 << 20)
+                                                 else 8192),
                    "launch": f"replays of one captured HIP graph of {args.graph_steps} iteration(s)" if args.graph else "one evg_step call per iteration",
                    "fraction_fired_full": f_full, "fraction_fired_topk": f_topk,
                    "messages_pct_of_regular": 100.0 * st["events_total"] / max(1, st["regular_events"]),

@@ -91,8 +91,10 @@ typedef struct {
                                    next iteration's drift norms (and the first radix
                                    histogram of its Top-K selection); EVG_NORM_SEPARATE:
                                    passes of their own read x and xhat                  */
-  uint32_t chunk_elems;         /* work granule of the send kernels: 0 (= 8192), 1024,
-                                   2048, 4096 or 8192 elements; no tensor shares one    */
+  uint32_t chunk_elems;         /* work granule of the send kernels: 1024, 2048, 4096 or
+                                   8192 elements, or 0 = chosen from the ring's size (2048
+                                   if the five arenas together take at most 128 MB, else
+                                   8192); no tensor shares one; results never differ     */
   uint32_t trigger_kind;        /* EVG_TRIGGER_DRIFT_NORM: test || x - xhat || (the formula of
                                    Section 4); EVG_TRIGGER_NORM_DIFF: test | ||x|| - ||xhat|| |
                                    (the wording of Section 4: "when the norm has changed by

@@ -244,8 +244,8 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   if (cfg->xhat_reset && cfg->delivery_delay)
     return fail(EVG_ERR_INVALID, "xhat_reset = 1 is not available with delivery_delay = 1");
   if (cfg->access_mode > EVG_ACCESS_CACHED) return fail(EVG_ERR_INVALID, "unknown access_mode %u", cfg->access_mode);
-  const uint32_t ce = cfg->chunk_elems ? cfg->chunk_elems : 8192u;
-  if (ce != 1024 && ce != 2048 && ce != 4096 && ce != 8192)
+  if (cfg->chunk_elems != 0 && cfg->chunk_elems != 1024 && cfg->chunk_elems != 2048 &&
+      cfg->chunk_elems != 4096 && cfg->chunk_elems != 8192)
     return fail(EVG_ERR_INVALID, "chunk_elems must be 0, 1024, 2048, 4096 or 8192");
   if (cfg->grad_mode == EVG_GRAD_SYNTH) {
     const evg_synth& s = cfg->synth;
@@ -262,6 +262,10 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   }
   const uint64_t Npad = evg_padded_numel(cfg->L, cfg->layer_numel);
   const uint64_t arena_bytes = (uint64_t)cfg->P * Npad * 4;
+  // rings that live in the last-level cache are bound by launch and workgroup counts, not by
+  // HBM: small granules leave fewer empty sweeps behind their many short tensors (measured)
+  const bool small_ring = 5 * arena_bytes <= (128ull << 20);
+  const uint32_t ce = cfg->chunk_elems ? cfg->chunk_elems : small_ring ? 2048u : 8192u;
   const float* arenas[5] = {cfg->x, cfg->xhat, cfg->mbox_l, cfg->mbox_r, cfg->vel};
   static const char* names[5] = {"x", "xhat", "mbox_l", "mbox_r", "vel"};
   for (int i = 0; i < 5; ++i) {
@@ -361,8 +365,7 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   HIP_OR_FREE(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   // 256 MB of last-level cache on MI355X; a ring whose arenas take at most half of it is
   // served from there and does better with ordinary than with streaming accesses
-  c->cached = cfg->access_mode == EVG_ACCESS_CACHED ||
-              (cfg->access_mode == EVG_ACCESS_AUTO && 5 * arena_bytes <= (128ull << 20));
+  c->cached = cfg->access_mode == EVG_ACCESS_CACHED || (cfg->access_mode == EVG_ACCESS_AUTO && small_ring);
   const uint64_t full_grid = (uint64_t)P * C;
   c->work_grid = (uint32_t)(full_grid < (uint64_t)cus * 8 ? full_grid : (uint64_t)cus * 8);
   TRY_OR_FREE(c->dalloc(&d_chunks, C, false));
