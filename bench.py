@@ -69,6 +69,9 @@ def main():
                          "1 = difference of the norms")
     ap.add_argument("--delivery-delay", type=int, default=0,
                     help="1 = messages land after the iteration's updates (not a benchmark configuration)")
+    ap.add_argument("--plain-sgd", action="store_true",
+                    help="momentum 0, the paper's optimiser (not a benchmark configuration): the velocity "
+                         "arena is then neither read nor written")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of captured evg_step_next calls instead of K evg_step calls "
                          "(same iterations; for the launch-bound small rings)")
@@ -89,6 +92,8 @@ def main():
     from paper_2103_07454_amd import evg, inputs
 
     w = inputs.config(args.config)
+    if args.plain_sgd:
+        w = w.scaled(momentum=0.0)
     x0 = w.x0()[None, :]                       # common start; uploaded once per worker slice
     x0 = np.broadcast_to(x0, (w.P, w.N))
 
@@ -168,7 +173,7 @@ def main():
     rho = w.topk_ppm / 1e6
     f_full = float((st["events_full_rl"].astype(np.float64) * numel[None, :]).sum() / (elems * args.steps))
     f_topk = float((st["events_topk_rl"].astype(np.float64) * numel[None, :]).sum() / (elems * args.steps))
-    step_bytes_per_elem = 28 + 16 * f_full + 8 * f_topk + 28 * rho * f_topk
+    step_bytes_per_elem = (28 if w.momentum != 0.0 else 20) + 16 * f_full + 8 * f_topk + 28 * rho * f_topk
     out = {
         "metric": "param_elements_per_s_fused_trigger_consensus_update",
         "value": elems * args.steps / dt,
@@ -180,7 +185,7 @@ def main():
         "config": {"workload": w.name + ("+DIAG_GRAD_BUFFER" if args.diag_grad_buffer else "")
                    + ("+NORM_DIFF_TRIGGER" if args.trigger_kind else "")
                    + ("+DELAYED_DELIVERY" if args.delivery_delay else "")
-                   + ("+XHAT_RESET" if args.xhat_reset else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
+                   + ("+XHAT_RESET" if args.xhat_reset else "") + ("+PLAIN_SGD" if args.plain_sgd else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
                    "threshold": "adaptive" if w.thr_mode else "fixed", "topk_ppm": w.topk_ppm,
                    "chunk_elems": args.chunk or (2048 if 5 * 4 * w.P * evg.padded_numel(w.layer_numel) <= (128 << 20)
                                                  else 8192),
@@ -197,6 +202,8 @@ def main():
         ms_upd, n_upd = phases["update"]
         avg_ms = ms_upd / max(1, n_upd)
         per_elem = UPDATE_BYTES_PER_ELEM + UPDATE_TOPK_BYTES_PER_FIRED_ELEM_PER_RHO * rho * f_topk
+        if w.momentum == 0.0:
+            per_elem -= 8          # plain SGD: no velocity read or write
         if args.trigger_kind == 1 and not w.topk_ppm:
             per_elem -= 4          # xhat is not read: its norm is a scalar per tensor
         upd_bytes = per_elem * elems

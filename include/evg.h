@@ -73,7 +73,8 @@ typedef struct {
   const uint64_t* layer_numel;  /* [L], each 1 .. 2^31-8; read during evg_init only     */
   const uint32_t* layer_fan_in; /* [L] or NULL when fan_in_scaling == 0                 */
   float lr;                     /* step size gamma (Eq. 2)                              */
-  float momentum;               /* 0 = the paper's plain SGD                            */
+  float momentum;               /* 0 = the paper's plain SGD: vel is then left at zero,
+                                   neither read nor written by evg_step                 */
   uint32_t thr_mode;            /* EVG_THR_FIXED: delta = thr_fixed for every tensor;
                                    EVG_THR_ADAPTIVE: Eq. 3                              */
   float thr_fixed;              /* >= 0; 0 and +inf are legal                           */
@@ -128,7 +129,7 @@ typedef struct {
   float* xhat;   /* values last sent (Section 4, X-hat)                   */
   float* mbox_l; /* last received from the left neighbour (r-1)           */
   float* mbox_r; /* last received from the right neighbour (r+1)          */
-  float* vel;    /* momentum buffer                                       */
+  float* vel;    /* momentum buffer (untouched after evg_init when momentum == 0) */
 } evg_config;
 
 /* Counters since evg_init (Section 7: share of messages, share of communication).

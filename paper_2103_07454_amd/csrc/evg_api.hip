@@ -520,6 +520,7 @@ static evg_status fixed_args(evg_ctx* c, const float* grad, StepArgs* out) {
   StepArgs a{};
   a.lr = g.lr;
   a.mu = g.momentum;
+  a.plain_sgd = g.momentum == 0.0f ? 1u : 0u;
   a.thr_mode = g.thr_mode;
   a.horizon = g.horizon;
   a.force_first = g.force_first ? 1u : 0u;

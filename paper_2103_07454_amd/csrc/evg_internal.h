@@ -91,6 +91,7 @@ struct StepArgs {
                            // and squared xhat in partials / partials_hat
   uint32_t delay;          // messages of this iteration land after its updates
   uint32_t hist_fused;     // the update pass of the previous iteration already built pass A's histograms
+  uint32_t plain_sgd;      // momentum == 0: the velocity arena is not touched
   uint32_t from_device;    // take k and decay^k from IterState instead of the two fields here
   uint32_t xhat_reset;     // a Top-K event resets the whole tensor's xhat to x
   uint32_t cached;         // the arenas fit the last-level cache: ordinary instead of streaming accesses

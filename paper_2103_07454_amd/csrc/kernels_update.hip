@@ -174,7 +174,9 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) { xa[u][i] = 0.f; va[u][i] = 0.f; la[u][i] = 0.f; ra[u][i] = 0.f; ha[u][i] = 0.f; g[u][i] = 0.f; }
       if (live[u]) {
-        const float4 x4 = ld4t<STREAM>(T.x + base + e[u]), v4 = ld4t<STREAM>(T.vel + base + e[u]);
+        const float4 x4 = ld4t<STREAM>(T.x + base + e[u]);
+        float4 v4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (!A.plain_sgd) v4 = ld4t<STREAM>(T.vel + base + e[u]);   // uniform
         xa[u][0] = x4.x; xa[u][1] = x4.y; xa[u][2] = x4.z; xa[u][3] = x4.w;
         va[u][0] = v4.x; va[u][1] = v4.y; va[u][2] = v4.z; va[u][3] = v4.w;
         if (vl) { const float4 t = ld4t<STREAM>(T.mbox_l + base + e[u]); la[u][0] = t.x; la[u][1] = t.y; la[u][2] = t.z; la[u][3] = t.w; }
@@ -253,7 +255,9 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           if ((uint32_t)i < nv) {   // lanes past the tensor's end are padding: left as they are
-            const float vn = __builtin_fmaf(A.mu, va[u][i], g[u][i]);
+            // momentum 0 is the paper's plain SGD: the velocity is the gradient, and the
+            // velocity arena is neither read nor written
+            const float vn = A.plain_sgd ? g[u][i] : __builtin_fmaf(A.mu, va[u][i], g[u][i]);
             const float a = (vl ? (la[u][i] - xa[u][i]) : 0.0f) + (vr ? (ra[u][i] - xa[u][i]) : 0.0f);
             const float cns = __builtin_fmaf(a, third, xa[u][i]);
             xa[u][i] = __builtin_fmaf(-A.lr, vn, cns);
@@ -261,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
           }
         }
         st4t<STREAM>(T.x + base + e[u], make_float4(xa[u][0], xa[u][1], xa[u][2], xa[u][3]));
-        st4t<STREAM>(T.vel + base + e[u], make_float4(va[u][0], va[u][1], va[u][2], va[u][3]));
+        if (!A.plain_sgd) st4t<STREAM>(T.vel + base + e[u], make_float4(va[u][0], va[u][1], va[u][2], va[u][3]));
         if (NORM == 1) drift_acc(acc[u], xa[u], ha[u], nv);
         if (NORM >= 2) square_acc(acc[u], xa[u], nv);
         if (NORM == 3) square_acc(acc_hat[u], ha[u], nv);

@@ -217,6 +217,7 @@ class Ring:
             self._h = h
         self.topk_ppm = topk_ppm
         self.access_mode = access_mode
+        self.momentum = float(momentum)
 
     @classmethod
     def from_workload(cls, w, x0=None, **over):

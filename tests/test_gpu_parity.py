@@ -82,7 +82,7 @@ def ragged(**kw):
 
 
 @pytest.mark.parametrize("chunk", [1024, 2048, 4096, 8192])
-@pytest.mark.parametrize("mode", ["fixed", "adaptive", "topk", "topk_value_key", "student_spike", "topk_xhat_reset", "topk_third"])
+@pytest.mark.parametrize("mode", ["fixed", "adaptive", "topk", "topk_value_key", "student_spike", "topk_xhat_reset", "topk_third", "plain_sgd", "plain_sgd_topk"])
 def test_ragged_all_modes(evg, oracle_mod, mode, chunk):
     kw = dict(fixed=dict(thr_mode=inputs.THR_FIXED, thr_fixed=6e-2), adaptive=dict(),
               topk=dict(topk_ppm=100_000), topk_value_key=dict(topk_ppm=50_000),
@@ -90,7 +90,9 @@ def test_ragged_all_modes(evg, oracle_mod, mode, chunk):
               topk_xhat_reset=dict(topk_ppm=100_000),
               # a third of every tensor: large chunks stage more than the staging kernel's LDS
               # buffer holds, some of them only in their second half
-              topk_third=dict(topk_ppm=333_333))[mode]
+              topk_third=dict(topk_ppm=333_333),
+              # momentum 0 (the paper's optimiser): the velocity arena is not touched at all
+              plain_sgd=dict(momentum=0.0), plain_sgd_topk=dict(momentum=0.0, topk_ppm=100_000))[mode]
     w = ragged(**kw)
     over = dict(topk_key=1) if mode == "topk_value_key" else dict(xhat_reset=1) if mode == "topk_xhat_reset" else {}
     ring, orc = pair(evg, oracle_mod, w, gpu=dict(chunk_elems=chunk), **over)
