@@ -51,8 +51,15 @@ def cpu_baseline(inputs, w, seconds_hint=20.0):
     for k in range(iters):
         orc.step(k)
     dt = time.perf_counter() - t0
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), model)
+    except OSError:
+        pass
     return {"value": P * ws.N * iters / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
-            "sample": f"{w.name} with P={P} ring workers, iterations 0..{iters - 1}, {dt:.1f} s"}
+            "sample": f"{w.name} with P={P} ring workers, iterations 0..{iters - 1}, {dt:.1f} s",
+            "host_cpu": model, "host_logical_cpus": os.cpu_count()}
 
 
 def main():
