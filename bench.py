@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--seed", type=int, default=None,
+                    help="seed of initial parameters and gradient streams (default: the configurations' own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-timers", action="store_true")
     ap.add_argument("--trigger-kind", type=int, default=0,
@@ -98,7 +100,7 @@ def main():
     import torch
     from paper_2103_07454_amd import evg, inputs
 
-    w = inputs.config(args.config)
+    w = inputs.config(args.config) if args.seed is None else inputs.config(args.config, args.seed)
     if args.plain_sgd:
         w = w.scaled(momentum=0.0)
     x0 = w.x0()[None, :]                       # common start; uploaded once per worker slice
@@ -192,7 +194,7 @@ def main():
         "config": {"workload": w.name + ("+DIAG_GRAD_BUFFER" if args.diag_grad_buffer else "")
                    + ("+NORM_DIFF_TRIGGER" if args.trigger_kind else "")
                    + ("+DELAYED_DELIVERY" if args.delivery_delay else "")
-                   + ("+XHAT_RESET" if args.xhat_reset else "") + ("+PLAIN_SGD" if args.plain_sgd else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N,
+                   + ("+XHAT_RESET" if args.xhat_reset else "") + ("+PLAIN_SGD" if args.plain_sgd else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N, "seed": w.seed,
                    "threshold": "adaptive" if w.thr_mode else "fixed", "topk_ppm": w.topk_ppm,
                    "chunk_elems": args.chunk or (2048 if 5 * 4 * w.P * evg.padded_numel(w.layer_numel) <= (128 << 20)
                                                  else 8192),
