@@ -37,14 +37,20 @@ UPDATE_TOPK_BYTES_PER_FIRED_ELEM_PER_RHO = 20
 # same command (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for
 # the library's plain copy kernel on a known size.  Source: profiles/.
 MEASURED_TRAFFIC_BYTES = {"cfg5_resnet18_p64_topk10pct": 26.5e9}
+# Vector-ALU instructions the update pass executes per element where its gradient generator,
+# not memory, bounds it (rocprofv3 --pmc SQ_INSTS_VALU x 64 lanes / elements; profiles/), and what
+# the chip can issue: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second.
+MEASURED_VALU_INSTS_PER_ELEMENT = {"cfg4_resnet50_p8_topk1pct_student_t": 302.0}
+ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 
 def cpu_baseline(inputs, w, seconds_hint=20.0):
     """The oracle as it stands, single thread, on a bounded sample of the same
     workload: fewer ring workers, first iterations."""
     import oracle
-    P, iters = 8, 5
+    P = 8
     ws = w.scaled(P=P)
+    iters = min(5, max(1, int(4e8 // (P * ws.N))))     # about 10-30 s of single-thread work
     x0 = inputs.replicate(ws.x0(), P)
     orc = oracle.Oracle.from_workload(ws, x0)
     t0 = time.perf_counter()
@@ -222,6 +228,13 @@ def main():
                            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
                            "avg_launch_ms": avg_ms, "launches": n_upd,
                            "algorithmic_bytes_per_launch": upd_bytes}
+        if w.name in MEASURED_VALU_INSTS_PER_ELEMENT:
+            ops = MEASURED_VALU_INSTS_PER_ELEMENT[w.name] * elems / (avg_ms * 1e-3) / 1e12
+            out["roofline"] = {"kernel": "k_update", "bound": "alu", "achieved": ops, "peak": ALU_PEAK_TLANEOPS,
+                               "unit": "T lane-instructions/s", "frac": ops / ALU_PEAK_TLANEOPS, "traffic": None,
+                               "avg_launch_ms": avg_ms, "launches": n_upd,
+                               "valu_instructions_per_element": MEASURED_VALU_INSTS_PER_ELEMENT[w.name],
+                               "hbm_achieved_GBps": achieved, "hbm_frac": achieved / HBM_PEAK_GBS}
         out["phase_ms_per_step"] = {p: ms / max(1, args.steps) for p, (ms, n) in phases.items()}
         # the other HBM-bound phases against the same peak, on their share of the lower-bound bytes:
         # whole sends move 12 B per fired element here (xhat := x rides in the update pass), the
@@ -261,7 +274,7 @@ def main():
     tri = 12.0 * n_tri / (ev0.elapsed_time(ev1) / avg_reps * 1e-3) / 1e9
     out["stream_triad"] = {"kind": "torch c = a + 0.5 b, fp32", "elements": n_tri, "GBps": tri,
                            "frac_of_hbm_peak": tri / HBM_PEAK_GBS}
-    if "roofline" in out:
+    if "roofline" in out and out["roofline"]["bound"] == "hbm":
         out["roofline"]["frac_of_triad"] = out["roofline"]["achieved"] / tri
     del ta, tb, tc
     torch.cuda.empty_cache()
