@@ -221,6 +221,16 @@ evg_status evg_last_decisions(evg_ctx* c, uint8_t* fired, uint8_t* near_tie, flo
 evg_status evg_message(evg_ctx* c, uint32_t r, uint32_t l, uint32_t* idx, float* val,
                        uint64_t cap, uint64_t* count);
 
+/* Fingerprints of the Top-K messages of the most recent step, HOST arrays of P*L entries,
+ * either may be NULL.  A message is K indices and K values (Section 7); for worker r,
+ * tensor l: idx_hash = sum over the message's entries of mix(index) and msg_hash = sum of
+ * mix(value bits << 32 | index), both modulo 2^64, with mix the finaliser of the SplitMix64
+ * generator (z += 0x9E3779B97F4A7C15; z = (z ^ z >> 30) * 0xBF58476D1CE4E5B9;
+ * z = (z ^ z >> 27) * 0x94D049BB133111EB; z ^ z >> 31).  0 where (r, l) sent no Top-K
+ * message.  They let a caller compare every message of a step with another implementation
+ * without copying the messages themselves to the host.  Waits for the stream. */
+evg_status evg_message_hashes(evg_ctx* c, uint64_t* idx_hash, uint64_t* msg_hash);
+
 /* Final model: out[j] = mean over workers of x[r][j] (last line of Algorithm B).
  * out: DEVICE array of evg_padded_numel floats.  Asynchronous on the stream. */
 evg_status evg_average(evg_ctx* c, float* out);

@@ -67,6 +67,9 @@ def lib():
         l.orc_totals.argtypes = [vp, u64p]
         l.orc_message.restype = C.c_uint64
         l.orc_message.argtypes = [vp, C.c_uint32, C.c_uint32, u32p, f32p, C.c_uint64]
+        l.orc_message_hashes.argtypes = [vp, u64p, u64p]
+        l.orc_splitmix64.restype = C.c_uint64
+        l.orc_splitmix64.argtypes = [C.c_uint64]
         l.orc_grad_tensor.argtypes = [vp, C.c_uint32, C.c_uint64, C.c_uint32, f32p]
         l.orc_average.argtypes = [vp, f32p]
         l.orc_philox4x32_10.argtypes = [u32p, u32p, u32p]
@@ -198,6 +201,13 @@ class Oracle:
             lib().orc_message(self._h, r, l, _p(idx, C.c_uint32), _p(val, C.c_float), n)
         return idx, val
 
+    def message_hashes(self):
+        """Fingerprints of the last step's Top-K messages, [P, L] uint64 each (0 = none)."""
+        PL = self.P * self.L
+        ih = np.zeros(PL, np.uint64); mh = np.zeros(PL, np.uint64)
+        lib().orc_message_hashes(self._h, _p(ih, C.c_uint64), _p(mh, C.c_uint64))
+        return ih.reshape(self.P, self.L), mh.reshape(self.P, self.L)
+
     def grad_tensor(self, r, k, l):
         out = np.empty(int(self._numel[l]), np.float32)
         lib().orc_grad_tensor(self._h, r, int(k), l, _p(out, C.c_float))
@@ -236,6 +246,10 @@ def normal4(w):
     a = np.ascontiguousarray(w, dtype=np.uint32); z = np.empty(4, np.float32)
     lib().orc_normal4(_p(a, C.c_uint32), _p(z, C.c_float))
     return z
+
+
+def splitmix64(z):
+    return int(lib().orc_splitmix64(int(z)))
 
 
 def topk_count(n, ppm):

@@ -196,6 +196,7 @@ struct Oracle {
   std::vector<Flight> in_flight;                // messages sent but not yet delivered (delay 1)
   std::vector<std::vector<uint32_t>> msg_idx;   // last Top-K message per (r,l)
   std::vector<std::vector<float>> msg_val;
+  std::vector<uint64_t> idx_hash, msg_hash;     // fingerprints of the last Top-K message per (r,l)
   uint64_t near_ties = 0, nonfinite = 0, iters = 0;
   int64_t last_iter = -1;
 
@@ -247,6 +248,15 @@ struct Oracle {
     if (sp) for (uint64_t j = 0; j < n; ++j) g[j] = g[j] * cfg.spike_gain;
   }
 };
+
+// 64-bit mixing function of the SplitMix64 generator (Steele, Lea, Flood, OOPSLA'14):
+// add the golden-ratio increment, then two xor-shift-multiply rounds and a last xor-shift.
+uint64_t splitmix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
 
 // The K largest keys under the total order (key descending, index ascending),
 // returned as ascending indices.
@@ -309,6 +319,7 @@ void* orc_create(const orc_config* cfg, const float* x0) {
   o->ev_full.assign(PL, 0); o->ev_topk.assign(PL, 0);
   o->slope_hist.assign(PL, {});
   o->msg_idx.assign(PL, {}); o->msg_val.assign(PL, {});
+  o->idx_hash.assign(PL, 0); o->msg_hash.assign(PL, 0);
   return o;
 }
 
@@ -362,6 +373,7 @@ int orc_step(void* h, uint64_t k, const float* grad_or_null, const int8_t* overr
         fire = override_or_null[s] != 0;
       o.fired[s] = 0;
       o.msg_idx[s].clear(); o.msg_val[s].clear();
+      o.idx_hash[s] = 0; o.msg_hash[s] = 0;
       if (!fire) continue;
 
       const bool first = o.last_event[s] < 0;
@@ -400,6 +412,10 @@ int orc_step(void* h, uint64_t k, const float* grad_or_null, const int8_t* overr
         topk_select(keys.data(), n, K, o.msg_idx[s]);
         for (uint32_t j : o.msg_idx[s]) {
           o.msg_val[s].push_back(xs[j]);
+          // fingerprints of the message (Section 7: K indices + K values): sums over its
+          // entries, so they do not depend on the order the entries are visited in
+          o.idx_hash[s] += splitmix64((uint64_t)j);
+          o.msg_hash[s] += splitmix64(((uint64_t)f2u(xs[j]) << 32) | (uint64_t)j);
           hs[j] = xs[j];
           if (now) { toR[j] = xs[j]; toL[j] = xs[j]; }
         }
@@ -521,6 +537,16 @@ uint64_t orc_message(void* h, uint32_t r, uint32_t l, uint32_t* idx, float* val,
   if (val) std::copy(o.msg_val[s].begin(), o.msg_val[s].begin() + n, val);
   return o.msg_idx[s].size();
 }
+
+// Fingerprints of the last step's Top-K messages, [P*L] each (0 where none was sent):
+// idx_hash = sum over the message's entries of splitmix64(index), msg_hash = the same over
+// (value bits << 32 | index), both modulo 2^64.
+void orc_message_hashes(void* h, uint64_t* idx_hash, uint64_t* msg_hash) {
+  Oracle& o = *(Oracle*)h;
+  if (idx_hash) std::copy(o.idx_hash.begin(), o.idx_hash.end(), idx_hash);
+  if (msg_hash) std::copy(o.msg_hash.begin(), o.msg_hash.end(), msg_hash);
+}
+uint64_t orc_splitmix64(uint64_t z) { return splitmix64(z); }
 
 // synthetic gradient of one tensor (for tests of the generator)
 void orc_grad_tensor(void* h, uint32_t r, uint64_t k, uint32_t l, float* out) {

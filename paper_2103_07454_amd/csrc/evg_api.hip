@@ -422,6 +422,8 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
     TRY_OR_FREE(c->dalloc(&t.chunk_sub, P * C * (t.SW + 1), true));
     TRY_OR_FREE(c->dalloc(&t.msg_idx, (uint64_t)P * ktot, true));
     TRY_OR_FREE(c->dalloc(&t.msg_val, (uint64_t)P * ktot, true));
+    TRY_OR_FREE(c->dalloc(&t.idx_hash, S, true));
+    TRY_OR_FREE(c->dalloc(&t.msg_hash, S, true));
   } else {
     t.work_topk = t.work_full;   // never listed: k_expand only writes it for Top-K events
   }
@@ -643,6 +645,22 @@ evg_status evg_message(evg_ctx* c, uint32_t r, uint32_t l, uint32_t* idx, float*
   if (idx && n) HIP_TRY(hipMemcpy(idx, t.msg_idx + base, n * 4, hipMemcpyDeviceToHost));
   if (val && n) HIP_TRY(hipMemcpy(val, t.msg_val + base, n * 4, hipMemcpyDeviceToHost));
   *count = K;
+  return EVG_OK;
+}
+
+evg_status evg_message_hashes(evg_ctx* c, uint64_t* idx_hash, uint64_t* msg_hash) {
+  if (!c) return fail(EVG_ERR_INVALID, "context is NULL");
+  const Tables& t = c->t;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  const bool live = c->cfg.topk_ppm && c->messages_live;
+  if (idx_hash) {
+    if (live) HIP_TRY(hipMemcpy(idx_hash, t.idx_hash, (size_t)t.S * 8, hipMemcpyDeviceToHost));
+    else std::memset(idx_hash, 0, (size_t)t.S * 8);
+  }
+  if (msg_hash) {
+    if (live) HIP_TRY(hipMemcpy(msg_hash, t.msg_hash, (size_t)t.S * 8, hipMemcpyDeviceToHost));
+    else std::memset(msg_hash, 0, (size_t)t.S * 8);
+  }
   return EVG_OK;
 }
 

@@ -68,6 +68,8 @@ struct Tables {
   uint32_t* chunk_sub;     // [P*C*(SW+1)] winners before each 1024-element sweep of a chunk,
                            // as message slots (entry 0 = the chunk's first slot)
   uint32_t* msg_idx; float* msg_val;          // [P*Ktot]
+  unsigned long long* idx_hash;               // [S] fingerprints of this step's Top-K messages:
+  unsigned long long* msg_hash;               // sums of mixed indices / mixed (value, index) pairs
   IterState* it;
   const double* decay_tab;   // decay^k for k < decay_len (replayable steps only)
   uint32_t decay_len;

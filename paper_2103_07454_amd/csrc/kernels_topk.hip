@@ -250,6 +250,22 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
   return __popcll(mask & ((1ull << lane_id()) - 1ull));
 }
 
+// Finaliser of the SplitMix64 generator (Steele, Lea, Flood, OOPSLA'14): used to turn a
+// message entry into 64 well-mixed bits, so that the sum over a message's entries is a
+// fingerprint of the message that does not depend on the order of summation.
+__device__ __forceinline__ unsigned long long mix64(unsigned long long z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
 constexpr int kBatch = 8;    // 64-entry groups loaded together by a wavefront, to overlap their latency
 
 // Bits 8..0 of the staged keys that carry the 22-bit prefix found so far.  Matches are
@@ -346,6 +362,7 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
     const uint32_t first = before.x + (before.y < ties ? before.y : ties);   // the chunk's first slot
     uint32_t run_g = before.x, run_e = before.y;
     uint32_t per_sweep[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // winners per sweep (wave-uniform)
+    unsigned long long hi = 0ull, hm = 0ull;            // this lane's share of the fingerprints
     for (uint32_t q0 = 0; q0 < ns; q0 += 64 * kBatch) {
       uint32_t key[kBatch], j[kBatch];
       float val[kBatch];
@@ -368,6 +385,8 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
           const uint32_t pos = g + (eq < ties ? eq : ties);
           T.msg_idx[mbase + pos] = j[u];
           T.msg_val[mbase + pos] = val[u];
+          hi += mix64((unsigned long long)j[u]);
+          hm += mix64(((unsigned long long)__float_as_uint(val[u]) << 32) | (unsigned long long)j[u]);
         }
         const uint32_t sw = (j[u] - wi.cd.j0) / (uint32_t)kSweep;
 #pragma unroll
@@ -377,7 +396,12 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
         run_e += __popcll(me);
       }
     }
+    // integer sums: the order in which chunks add their shares does not change the result
+    hi = wave_sum_u64(hi);
+    hm = wave_sum_u64(hm);
     if (lane_id() == 0) {
+      atomicAdd(&T.idx_hash[wi.seg], hi);
+      atomicAdd(&T.msg_hash[wi.seg], hm);
       uint32_t at = first;
 #pragma unroll
       for (uint32_t s2 = 0; s2 < 8; ++s2)

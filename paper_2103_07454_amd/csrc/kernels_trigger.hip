@@ -80,6 +80,7 @@ __device__ __forceinline__ void trigger_segment(const Tables& T, const StepArgs&
     }
   }
   T.fired[seg] = code;
+  if (A.topk_on) { T.idx_hash[seg] = 0ull; T.msg_hash[seg] = 0ull; }   // k_topk_pack adds to them
 }
 
 __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {

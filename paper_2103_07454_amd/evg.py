@@ -26,7 +26,7 @@ TRIGGER_DRIFT_NORM, TRIGGER_NORM_DIFF = 0, 1
 PHASES = ("norm", "trigger", "send_full", "topk_select", "topk_send", "update", "deliver")
 
 EXPORTS = ("evg_padded_numel", "evg_layer_offsets", "evg_init", "evg_step", "evg_step_next", "evg_stats",
-           "evg_last_decisions", "evg_message", "evg_average", "evg_state_size", "evg_state_export",
+           "evg_last_decisions", "evg_message", "evg_message_hashes", "evg_average", "evg_state_size", "evg_state_export",
            "evg_state_import", "evg_timing", "evg_timing_read",
            "evg_destroy", "evg_strerror", "evg_error_text")
 
@@ -91,6 +91,7 @@ def lib():
         l.evg_stats.argtypes = [vp, C.POINTER(Stats)]
         l.evg_last_decisions.argtypes = [vp, vp, vp, vp, vp]
         l.evg_message.argtypes = [vp, C.c_uint32, C.c_uint32, vp, vp, C.c_uint64, u64p]
+        l.evg_message_hashes.argtypes = [vp, vp, vp]
         l.evg_average.argtypes = [vp, vp]
         l.evg_state_size.restype = C.c_uint64
         l.evg_state_size.argtypes = [vp]
@@ -280,6 +281,13 @@ class Ring:
         if n.value:
             _check(lib().evg_message(self._h, r, l, idx.ctypes.data, val.ctypes.data, n.value, C.byref(n)))
         return idx, val
+
+    def message_hashes(self):
+        """Fingerprints of the last step's Top-K messages: two [P, L] uint64 arrays."""
+        S = self.P * self.L
+        ih = np.zeros(S, np.uint64); mh = np.zeros(S, np.uint64)
+        _check(lib().evg_message_hashes(self._h, ih.ctypes.data, mh.ctypes.data))
+        return ih.reshape(self.P, self.L), mh.reshape(self.P, self.L)
 
     def state(self, name) -> np.ndarray:
         """[P, N] host copy of an arena with the padding removed."""

@@ -44,6 +44,18 @@ def lockstep(ring, orc, iters, *, grads=None, gpu_grads=None, sample_messages=32
                                f"gpu norm {gd['norm'][bad][:5]} oracle norm {od['norm'][bad][:5]} "
                                f"delta {od['delta_before'][bad][:5]}")
         replayed += int(((od["near_tie"] != 0) & (gd["near_tie"] != 0)).sum())
+        # the 1e-6 band is the only licence for a disagreement, so both sides must agree on where
+        # it lies (a flag may differ only where the norms themselves differ in their last bit)
+        nt_diff = (gd["near_tie"] != 0) != (od["near_tie"] != 0)
+        assert not (nt_diff & (gd["norm"] == od["norm"]) & (gd["delta_before"] == od["delta_before"])).any(), \
+            f"iteration {k}: near-tie flags differ at {np.argwhere(nt_diff)[:5].tolist()}"
+        if getattr(ring, "topk_ppm", 0):
+            # every Top-K message of the iteration, through its fingerprints
+            gih, gmh = ring.message_hashes()
+            oih, omh = orc.message_hashes()
+            assert np.array_equal(gih, oih), f"iteration {k}: Top-K index sets differ at {np.argwhere(gih != oih)[:5].tolist()}"
+            assert np.array_equal(gmh, omh), f"iteration {k}: Top-K message values differ at {np.argwhere(gmh != omh)[:5].tolist()}"
+            assert ((gih != 0) == (gd["fired"] == 2)).all()
         # norms agree to summation-order rounding; thresholds likewise
         if norm_rtol is not None:
             np.testing.assert_allclose(gd["norm"], od["norm"], rtol=norm_rtol, atol=1e-37, equal_nan=True)
@@ -74,6 +86,8 @@ def lockstep(ring, orc, iters, *, grads=None, gpu_grads=None, sample_messages=32
     tot = orc.totals()
     for key in ("events_total", "value_words", "index_words", "bytes_sent", "nonfinite_norms", "iters"):
         assert gs[key] == tot[key], (key, gs[key], tot[key])
+    if norm_rtol is not None and replayed == 0:
+        assert gs["near_tie_flags"] == tot["near_tie_flags"], (gs["near_tie_flags"], tot["near_tie_flags"])
     gm = masked_mailboxes(ring, gs, numel)
     om = masked_mailboxes(orc, tb, numel)
     for name in ARENAS:

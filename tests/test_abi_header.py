@@ -25,7 +25,7 @@ def test_header_compiles_as_c99(tmp_path):
           (void)evg_stats; (void)evg_last_decisions; (void)evg_message; (void)evg_average;
           (void)evg_state_size; (void)evg_state_export; (void)evg_state_import;
           (void)evg_timing; (void)evg_timing_read; (void)evg_destroy; (void)evg_strerror;
-          (void)evg_error_text;
+          (void)evg_error_text; (void)evg_step_next; (void)evg_message_hashes;
           return ctx != NULL;
         }
     """))
