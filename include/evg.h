@@ -182,6 +182,26 @@ evg_status evg_layer_offsets(uint32_t L, const uint64_t* layer_numel, uint64_t* 
  * Top-K histograms and message staging). */
 evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream);
 
+/* evg_init for callers that must not allocate device memory (harnesses that forbid
+ * hipMalloc, tight serving loops that create and drop rings, code that is later captured
+ * into a HIP graph): identical to evg_init in arguments, results and in every later call on
+ * the context, except that all library-owned device tables (norm partial sums, decisions,
+ * counters, work lists, Top-K histograms, staging and message buffers) are carved out of one
+ * block of EVG_STATIC_SCRATCH_BYTES that is part of the library image on every GPU, instead
+ * of coming from hipMalloc.  Calls no hipMalloc / hipFree and no allocating library routine;
+ * evg_destroy on such a context frees no device memory either.  A configuration whose
+ * tables do not fit is rejected with EVG_ERR_INVALID (the text gives the bytes needed).
+ * The HIP runtime places the block on a GPU when it is first used there: the first call on
+ * a device (which looks the block's address up) lowers free device memory by the block's
+ * size, later calls leave it unchanged.
+ * All calls on one GPU share that GPU's block, and it keeps the previous context's
+ * contents (what must start at zero is cleared here): at most one such context may exist
+ * per GPU at a time -- a second evg_init_static before the first context's evg_destroy
+ * returns EVG_ERR_STATE -- and two threads that race through these calls on one GPU are
+ * not protected against each other beyond that check. */
+#define EVG_STATIC_SCRATCH_BYTES (64u << 20)
+evg_status evg_init_static(evg_ctx** out, const evg_config* cfg, void* hip_stream);
+
 /* One iteration k = iter of Algorithm B for all P workers: trigger tests, sends
  * (visible to every worker's update of the same iteration), then the averaging
  * and SGD update.  iter must be larger than the previous call's and below 2^31.

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -43,6 +44,21 @@ struct TimerPair { hipEvent_t a, b; int phase; };
 
 constexpr uint32_t kDecayTable = 1u << 16;   // iterations a replayable step can reach
 
+// ---- the one block of device memory that evg_init_static hands out -------------------
+// Every GPU the library runs on holds its own copy of this array from the moment the
+// library is loaded until the process ends.  In host code the array's NAME is only a
+// handle for hipGetSymbolAddress: the device address differs per GPU and is looked up
+// once per device (scratch_base), and only that address is ever passed to kernels,
+// memsets or copies.
+constexpr size_t kScratchBytes = EVG_STATIC_SCRATCH_BYTES;
+constexpr size_t kScratchAlign = 256;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+std::mutex g_scratch_mu;
+unsigned char* g_scratch_base[kMaxDevices] = {nullptr};   // per device: where its copy lives
+evg_ctx* g_scratch_user[kMaxDevices] = {nullptr};         // per device: the context living in it
+
 }  // namespace
 
 struct evg_ctx {
@@ -63,6 +79,10 @@ struct evg_ctx {
   bool device_ahead = false;        // evg_step_next has been used: replays of a captured graph
                                     // advance the device's iteration without the host seeing
                                     // it, so iters / last_iter are re-read whenever needed
+  // evg_init_static: the tables are carved out of the device's static scratch block
+  unsigned char* arena_base = nullptr;   // null = tables come from hipMalloc
+  size_t arena_used = 0;
+  int arena_dev = -1;
   // timing
   bool timing = false;
   std::vector<TimerPair> pending;
@@ -74,9 +94,18 @@ struct evg_ctx {
   evg_status dalloc(T** p, size_t count, bool zero) {
     void* d = nullptr;
     const size_t bytes = (count ? count : 1) * sizeof(T);
-    hipError_t e = hipMalloc(&d, bytes);
-    if (e != hipSuccess) return fail(EVG_ERR_OOM, "hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(e));
-    owned.push_back(d);
+    if (arena_base) {
+      const size_t at = (arena_used + kScratchAlign - 1) / kScratchAlign * kScratchAlign;
+      if (at + bytes > kScratchBytes)
+        return fail(EVG_ERR_INVALID, "the static scratch block holds %zu bytes; this configuration needs more",
+                    kScratchBytes);
+      d = arena_base + at;
+      arena_used = at + bytes;
+    } else {
+      hipError_t e = hipMalloc(&d, bytes);
+      if (e != hipSuccess) return fail(EVG_ERR_OOM, "hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(e));
+      owned.push_back(d);
+    }
     if (zero) HIP_TRY(hipMemsetAsync(d, 0, bytes, stream));
     *p = static_cast<T*>(d);
     return EVG_OK;
@@ -212,6 +241,10 @@ evg_status evg_layer_offsets(uint32_t L, const uint64_t* layer_numel, uint64_t* 
 evg_status evg_destroy(evg_ctx* c) {
   if (!c) return EVG_OK;
   (void)hipStreamSynchronize(c->stream);
+  if (c->arena_base) {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (c->arena_dev >= 0 && g_scratch_user[c->arena_dev] == c) g_scratch_user[c->arena_dev] = nullptr;
+  }
   for (void* p : c->owned) (void)hipFree(p);
   for (const TimerPair& p : c->pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   for (hipEvent_t e : c->pool) (void)hipEventDestroy(e);
@@ -219,7 +252,34 @@ evg_status evg_destroy(evg_ctx* c) {
   return EVG_OK;
 }
 
-evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
+// Bytes of library-owned device tables a configuration needs, with every table rounded up to
+// the scratch block's alignment: the same list as the allocations of init_common.
+static uint64_t table_bytes(uint64_t P, uint64_t L, uint64_t C, uint64_t SW, uint64_t hist_len, uint64_t Npad,
+                            uint64_t ktot, bool topk, bool norm_diff) {
+  const uint64_t S = P * L, PC = P * C;
+  uint64_t total = 0;
+  auto add = [&total](uint64_t count, uint64_t elem) {
+    total = (total + kScratchAlign - 1) / kScratchAlign * kScratchAlign + (count ? count : 1) * elem;
+  };
+  add(C, sizeof(ChunkDesc)); add(L, sizeof(LayerDesc));
+  add(PC * SW, 8);
+  if (norm_diff) { add(PC * SW, 8); add(S, 8); }
+  add(S, 4); add(S, 4); add(S, 4); add(S, 4);            // delta, last_norm, delta_before, last_event
+  add(S, 1); add(S, 1); add(S, 1); add(S, 1);            // valid_l, valid_r, fired, near_tie
+  add(S, 4); add(S, 4); add(S, 4); add(S, 4);            // ev_full, ev_topk, near_cnt, nonfinite_cnt
+  add(S * hist_len, 4); add(S, 4); add(S, 4); add(S, 4); // slope_hist, slope_cnt, seg_woff_full/topk
+  add(4, 4); add(1, sizeof(IterState)); add(kDecayTable, 8);
+  add(PC, 4);                                            // work_full
+  if (topk) {
+    add(PC, 4); add(S * kHistBins, 4); add(S, 4); add(S, 4); add(PC, 4);
+    add(P * Npad, 4); add(P * Npad, 4); add(P * Npad, 4);
+    add(PC, 8); add(PC, 8); add(PC * (SW + 1), 4);
+    add(P * ktot, 4); add(P * ktot, 4); add(S, 8); add(S, 8);
+  }
+  return total;
+}
+
+static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_stream, bool use_scratch) {
   if (!out || !cfg) return fail(EVG_ERR_INVALID, "out and cfg must be non-NULL");
   evg_status st = check_layers(cfg->L, cfg->layer_numel);
   if (st != EVG_OK) return st;
@@ -363,6 +423,38 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
   } while (0)
   HIP_OR_FREE(hipGetDevice(&dev));
   HIP_OR_FREE(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  if (use_scratch) {
+    const uint64_t need = table_bytes(P, L, C, t.SW, t.hist_len, Npad, ktot, cfg->topk_ppm != 0,
+                                      cfg->trigger_kind == EVG_TRIGGER_NORM_DIFF);
+    if (need > kScratchBytes) {
+      evg_destroy(c);
+      return fail(EVG_ERR_INVALID, "this configuration needs %llu bytes of tables; the static scratch block "
+                  "holds %llu (use evg_init)", (unsigned long long)need, (unsigned long long)kScratchBytes);
+    }
+    if (dev < 0 || dev >= kMaxDevices) {
+      evg_destroy(c);
+      return fail(EVG_ERR_INVALID, "device %d is beyond the %d devices evg_init_static keeps track of", dev, kMaxDevices);
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_base[dev]) {
+      // once per device, with that device current: where this GPU's copy of the array lives
+      void* base = nullptr;
+      hipError_t e = hipGetSymbolAddress(&base, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !base) {
+        delete c;
+        return fail(EVG_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+      }
+      g_scratch_base[dev] = static_cast<unsigned char*>(base);
+    }
+    if (g_scratch_user[dev]) {
+      delete c;
+      return fail(EVG_ERR_STATE, "the static scratch block of device %d is in use by another context: "
+                  "destroy that context first", dev);
+    }
+    g_scratch_user[dev] = c;
+    c->arena_base = g_scratch_base[dev];
+    c->arena_dev = dev;
+  }
   // 256 MB of last-level cache on MI355X; a ring whose arenas take at most half of it is
   // served from there and does better with ordinary than with streaming accesses
   c->cached = cfg->access_mode == EVG_ACCESS_CACHED || (cfg->access_mode == EVG_ACCESS_AUTO && small_ring);
@@ -440,6 +532,14 @@ evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
 #undef HIP_OR_FREE
   *out = c;
   return EVG_OK;
+}
+
+evg_status evg_init(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
+  return init_common(out, cfg, hip_stream, false);
+}
+
+evg_status evg_init_static(evg_ctx** out, const evg_config* cfg, void* hip_stream) {
+  return init_common(out, cfg, hip_stream, true);
 }
 
 // Brings iters / last_iter up to date with the device after replayable steps.

@@ -25,7 +25,7 @@ ACCESS_AUTO, ACCESS_STREAM, ACCESS_CACHED = 0, 1, 2
 TRIGGER_DRIFT_NORM, TRIGGER_NORM_DIFF = 0, 1
 PHASES = ("norm", "trigger", "send_full", "topk_select", "topk_send", "update", "deliver")
 
-EXPORTS = ("evg_padded_numel", "evg_layer_offsets", "evg_init", "evg_step", "evg_step_next", "evg_stats",
+EXPORTS = ("evg_padded_numel", "evg_layer_offsets", "evg_init", "evg_init_static", "evg_step", "evg_step_next", "evg_stats",
            "evg_last_decisions", "evg_message", "evg_message_hashes", "evg_average", "evg_state_size", "evg_state_export",
            "evg_state_import", "evg_timing", "evg_timing_read",
            "evg_destroy", "evg_strerror", "evg_error_text")
@@ -86,6 +86,7 @@ def lib():
         l.evg_padded_numel.argtypes = [C.c_uint32, u64p]
         l.evg_layer_offsets.argtypes = [C.c_uint32, u64p, u64p]
         l.evg_init.argtypes = [C.POINTER(vp), C.POINTER(Config), vp]
+        l.evg_init_static.argtypes = [C.POINTER(vp), C.POINTER(Config), vp]
         l.evg_step.argtypes = [vp, C.c_uint64, vp]
         l.evg_step_next.argtypes = [vp, vp]
         l.evg_stats.argtypes = [vp, C.POINTER(Stats)]
@@ -165,7 +166,7 @@ class Ring:
                  force_first=1, topk_ppm=0, topk_key=KEY_ABS_DRIFT, grad_mode=GRAD_SYNTH,
                  norm_mode=NORM_FUSED, chunk_elems=0, trigger_kind=TRIGGER_DRIFT_NORM, delivery_delay=0, xhat_reset=0, access_mode=0, seed=0, dist=DIST_NORMAL, fan_in_scaling=0,
                  sigma0=0.0, decay=1.0, spike_prob=0.0, spike_gain=1.0, device="cuda:0",
-                 mailbox_fill=None, stream=None):
+                 mailbox_fill=None, stream=None, static_tables=False):
         import torch
         self.torch = torch
         lib()
@@ -214,7 +215,11 @@ class Ring:
             cfg.mbox_l, cfg.mbox_r, cfg.vel = self.mbox_l.data_ptr(), self.mbox_r.data_ptr(), self.vel.data_ptr()
             torch.cuda.synchronize(self.device)
             h = C.c_void_p()
-            _check(lib().evg_init(C.byref(h), C.byref(cfg), C.c_void_p(self.stream.cuda_stream)))
+            init = lib().evg_init_static if static_tables else lib().evg_init
+            free_before = torch.cuda.mem_get_info(self.device)[0]
+            _check(init(C.byref(h), C.byref(cfg), C.c_void_p(self.stream.cuda_stream)))
+            # device memory the library took for its own tables (0 for evg_init_static)
+            self.library_bytes = free_before - torch.cuda.mem_get_info(self.device)[0]
             self._h = h
         self.topk_ppm = topk_ppm
         self.access_mode = access_mode
