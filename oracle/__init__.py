@@ -49,7 +49,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        l = C.CDLL(build())
+        # EVG_ORACLE_LIB: load this build of the oracle instead (the planted-mistake test points
+        # it at deliberately broken copies to show that the pins notice them)
+        l = C.CDLL(os.environ.get("EVG_ORACLE_LIB") or build())
         vp, u8p, f32p = C.c_void_p, C.POINTER(C.c_uint8), C.POINTER(C.c_float)
         u32p, u64p, i32p, i8p = (C.POINTER(C.c_uint32), C.POINTER(C.c_uint64),
                                  C.POINTER(C.c_int32), C.POINTER(C.c_int8))
