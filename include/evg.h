@@ -79,8 +79,9 @@ typedef struct {
                                    EVG_THR_ADAPTIVE: Eq. 3                              */
   float thr_fixed;              /* >= 0; 0 and +inf are legal                           */
   float horizon;                /* h of Eq. 3 (1 in the paper's experiments)            */
-  uint32_t hist_len;            /* 1 = Eq. 3 as printed; up to 16 = mean of the slopes
-                                   between the last hist_len events (Section 7)        */
+  uint32_t hist_len;            /* slopes kept per tensor, 1 .. 16: the threshold is h times the
+                                   mean of the last hist_len slopes, one slope per event (they
+                                   span hist_len + 1 events); 1 = Eq. 3 as printed (Section 7) */
   float delta_init;             /* adaptive threshold before a tensor's first event     */
   uint32_t force_first;         /* nonzero: every tensor sends at iteration 0 (Section 4) */
   uint32_t topk_ppm;            /* 0 = whole tensors; else K = max(1, ceil(n*ppm/1e6))
@@ -98,8 +99,8 @@ typedef struct {
                                    8192); no tensor shares one; results never differ     */
   uint32_t trigger_kind;        /* EVG_TRIGGER_DRIFT_NORM: test || x - xhat || (the formula of
                                    Section 4); EVG_TRIGGER_NORM_DIFF: test | ||x|| - ||xhat|| |
-                                   (the wording of Section 4: "when the norm has changed by
-                                   some threshold"); Eq. 3 then uses the same quantity      */
+                                   (Section 4's prose reading: the change of the norm itself);
+                                   Eq. 3 then uses the same quantity                         */
   uint32_t delivery_delay;      /* 0: a message is visible to the updates of the iteration it is
                                    sent in; 1: it lands after them and is used from the next
                                    iteration on (a deterministic stand-in for the asynchrony of

@@ -25,15 +25,27 @@ def masked_mailboxes(ring_or_oracle, valid, numel):
 
 
 def lockstep(ring, orc, iters, *, grads=None, gpu_grads=None, sample_messages=32, seed=0,
-             check_every=None, progress=None, say=print, norm_rtol=2e-7):
+             check_every=None, progress=None, say=print, norm_rtol=2e-7, norm_abs_of_x=None):
     """Steps both sides through ``iters`` iterations.  After every iteration the
     decisions must agree exactly; a disagreement is tolerated only where both
     sides flag a near tie (|norm - delta| < 1e-6 delta), in which case the oracle
-    follows the GPU's decision.  Returns a report dict."""
+    follows the GPU's decision.  Returns a report dict.
+
+    norm_rtol: relative bound on the tested norms and thresholds (drift-norm trigger: both sides
+    sum exact double products and differ by summation order only).  norm_abs_of_x: for the
+    norm-difference trigger, whose tested quantity | ||x|| - ||xhat|| | is a difference of two
+    rounded norms and so carries an absolute error of a few float spacings of ||x||: the bound is
+    norm_abs_of_x * ||x|| per (worker, tensor)."""
     rng = np.random.default_rng(seed)
     replayed = 0
     numel = np.asarray(orc._numel, np.int64)
+    xnorm_max = None
     for k in range(iters):
+        if norm_abs_of_x is not None:
+            xs = orc.state("x").astype(np.float64)
+            off = np.concatenate([[0], np.cumsum(numel)])
+            xn = np.stack([np.sqrt((xs[:, off[l]:off[l + 1]] ** 2).sum(axis=1)) for l in range(numel.size)], axis=1)
+            xnorm_max = xn if xnorm_max is None else np.maximum(xnorm_max, xn)
         ring.step(k, grad=None if gpu_grads is None else gpu_grads(k))
         gd = ring.decisions()
         override = np.where(gd["near_tie"] != 0, (gd["fired"] > 0).astype(np.int8), np.int8(-1)).astype(np.int8)
@@ -60,6 +72,14 @@ def lockstep(ring, orc, iters, *, grads=None, gpu_grads=None, sample_messages=32
         if norm_rtol is not None:
             np.testing.assert_allclose(gd["norm"], od["norm"], rtol=norm_rtol, atol=1e-37, equal_nan=True)
             np.testing.assert_allclose(gd["delta_before"], od["delta_before"], rtol=2 * norm_rtol, atol=1e-37)
+        if norm_abs_of_x is not None:
+            err = np.abs(gd["norm"].astype(np.float64) - od["norm"].astype(np.float64))
+            assert (err <= norm_abs_of_x * xn + 1e-37).all(), (k, float((err / np.maximum(xn, 1e-300)).max()))
+            # a threshold is h times a mean of tested norms, each divided by an iteration count >= 1
+            # (Eq. 3; h <= 2 in every test that uses this bound), plus the rounding of that mean
+            err = np.abs(gd["delta_before"].astype(np.float64) - od["delta_before"].astype(np.float64))
+            bound = 2 * norm_abs_of_x * xnorm_max + 4e-7 * np.abs(od["delta_before"].astype(np.float64)) + 1e-37
+            assert (err <= bound).all(), k
         if sample_messages:
             rs, ls = np.nonzero(gd["fired"] == 2)
             if rs.size:
@@ -92,7 +112,9 @@ def lockstep(ring, orc, iters, *, grads=None, gpu_grads=None, sample_messages=32
     om = masked_mailboxes(orc, tb, numel)
     for name in ARENAS:
         if name == "vel" and getattr(ring, "momentum", 1.0) == 0.0:
-            # plain SGD: the library leaves its velocity arena at zero (the oracle's holds the last gradient)
+            # plain SGD: the library leaves its velocity arena at zero, the oracle's holds the last
+            # gradient.  That gradient is still checked: x' = fma(-lr, g, c) with c equal on both
+            # sides, so the bitwise comparison of x below fails if the two sides drew different g
             assert not ring.state("vel").any()
             continue
         g = gm[name] if name in gm else ring.state(name)
