@@ -33,24 +33,34 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak, GB/s
 UPDATE_BYTES_PER_ELEM = 28
 UPDATE_TOPK_BYTES_PER_FIRED_ELEM_PER_RHO = 20
 
-# Average HBM bytes of one k_update launch, from two rocprofv3 --pmc runs of this
-# same command (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for
-# the library's plain copy kernel on a known size.  Source: profiles/.
-MEASURED_TRAFFIC_BYTES = {"cfg5_resnet18_p64_topk10pct": 26.5e9}
-# Vector-ALU instructions the update pass executes per element where its gradient generator,
-# not memory, bounds it (rocprofv3 --pmc SQ_INSTS_VALU x 64 lanes / elements; profiles/), and what
-# the chip can issue: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second.
-MEASURED_VALU_INSTS_PER_ELEMENT = {"cfg4_resnet50_p8_topk1pct_student_t": 302.0}
+# Counter figures (HBM bytes of one k_update launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE;
+# vector-ALU instructions per element from SQ_INSTS_VALU) are not typed in here: they are read from
+# profiles/counters_<workload>.json, which `python -m paper_2103_07454_amd.rocprof_summary` writes from
+# the profiler's output together with the step count and fired share they were measured at.
+# What the chip can issue: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second.
 ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+
+def measured_counters(workload):
+    """The tracked counter summary of this workload, or None if none has been recorded."""
+    path = os.path.join(ROOT, "profiles", f"counters_{workload}.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        rec = json.load(f)
+    rec["file"] = os.path.relpath(path, ROOT)
+    return rec
 
 
 def cpu_baseline(inputs, w, seconds_hint=20.0):
     """The oracle as it stands, single thread, on a bounded sample of the same
-    workload: fewer ring workers, first iterations."""
+    workload: a ring of 4 of its workers (the oracle's cost per element does not depend on the
+    ring size), first iterations -- as many as fit 10-30 s, so that the two all-fire iterations
+    0 and 1 weigh as little as the bound allows."""
     import oracle
-    P = 8
+    P = min(4, w.P)
     ws = w.scaled(P=P)
-    iters = min(5, max(1, int(4e8 // (P * ws.N))))     # about 10-30 s of single-thread work
+    iters = min(20, max(2, int(4.5e8 // (P * ws.N))))     # about 10-30 s of single-thread work
     x0 = inputs.replicate(ws.x0(), P)
     orc = oracle.Oracle.from_workload(ws, x0)
     t0 = time.perf_counter()
@@ -223,17 +233,44 @@ def main():
             per_elem -= 4          # xhat is not read: its norm is a scalar per tensor
         upd_bytes = per_elem * elems
         achieved = upd_bytes / (avg_ms * 1e-3) / 1e9
+        # What the dense-mailbox semantics cost at the granularity memory is written in: the dense
+        # 28 (or fewer) bytes per element, xhat := x for whole sends, each message read by its
+        # sender and both receivers (3 x 8 bytes per entry), and the write-back of every aligned
+        # 64-byte group of xhat and of the two mailboxes that holds a sent entry.  With K of n
+        # entries sent, spread evenly, a 16-float group holds one with probability 1 - (1 - K/n)^16.
+        dense = per_elem - UPDATE_TOPK_BYTES_PER_FIRED_ELEM_PER_RHO * rho * f_topk
+        ev_topk = st["events_topk_rl"].astype(np.float64).sum(axis=0)        # per tensor, all workers and steps
+        K = np.array([max(1, min(int(n), -(-int(n) * w.topk_ppm // 1_000_000))) if w.topk_ppm else 0
+                      for n in w.layer_numel], np.float64)
+        share = K / numel
+        dirty = 1.0 - (1.0 - share) ** 16
+        floor = dense * elems + 4 * f_full * elems + float((ev_topk * numel * (12 * dirty + 24 * share)).sum()) / args.steps
+        counters = measured_counters(w.name) if not (args.diag_grad_buffer or args.trigger_kind or args.delivery_delay
+                                                     or args.xhat_reset or args.plain_sgd or args.seed is not None) else None
+        upd_counters = (counters or {}).get("kernels", {}).get("k_update", {})
+        traffic = upd_counters.get("traffic_bytes")
         out["roofline"] = {"kernel": "k_update", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                           "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                           "traffic": traffic,
+                           "traffic_measured_at": None if traffic is None else {
+                               "file": counters["file"], "steps": counters["steps"],
+                               "fraction_fired_topk": counters["fraction_fired_topk"],
+                               "fraction_fired_full": counters["fraction_fired_full"]},
                            "avg_launch_ms": avg_ms, "launches": n_upd,
-                           "algorithmic_bytes_per_launch": upd_bytes}
-        if w.name in MEASURED_VALU_INSTS_PER_ELEMENT:
-            ops = MEASURED_VALU_INSTS_PER_ELEMENT[w.name] * elems / (avg_ms * 1e-3) / 1e12
+                           "algorithmic_bytes_per_launch": upd_bytes,
+                           "line_granular_floor_bytes_per_launch": floor,
+                           "floor_over_algorithmic": floor / upd_bytes,
+                           "traffic_over_floor": None if traffic is None else traffic / floor,
+                           "achieved_on_floor_GBps": floor / (avg_ms * 1e-3) / 1e9}
+        valu = upd_counters.get("valu_instructions_per_element")
+        if valu is not None and w.dist == 1:
+            # Student-t gradients: the generator, not memory, bounds the pass
+            ops = valu * elems / (avg_ms * 1e-3) / 1e12
             out["roofline"] = {"kernel": "k_update", "bound": "alu", "achieved": ops, "peak": ALU_PEAK_TLANEOPS,
                                "unit": "T lane-instructions/s", "frac": ops / ALU_PEAK_TLANEOPS, "traffic": None,
                                "avg_launch_ms": avg_ms, "launches": n_upd,
-                               "valu_instructions_per_element": MEASURED_VALU_INSTS_PER_ELEMENT[w.name],
+                               "valu_instructions_per_element": valu,
+                               "valu_measured_at": {"file": counters["file"]},
                                "hbm_achieved_GBps": achieved, "hbm_frac": achieved / HBM_PEAK_GBS}
         out["phase_ms_per_step"] = {p: ms / max(1, args.steps) for p, (ms, n) in phases.items()}
         # the other HBM-bound phases against the same peak, on their share of the lower-bound bytes:

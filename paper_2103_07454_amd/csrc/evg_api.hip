@@ -271,7 +271,7 @@ static uint64_t table_bytes(uint64_t P, uint64_t L, uint64_t C, uint64_t SW, uin
   add(4, 4); add(1, sizeof(IterState)); add(kDecayTable, 8);
   add(PC, 4);                                            // work_full
   if (topk) {
-    add(PC, 4); add(S * kHistBins, 4); add(S, 4); add(S, 4); add(PC, 4);
+    add(PC, 4); add(S * kHistBins, 4); add(S, 4); add(S, 4); add(PC, 8);
     add(P * Npad, 4); add(P * Npad, 4); add(P * Npad, 4);
     add(PC, 8); add(PC, 8); add(PC * (SW + 1), 4);
     add(P * ktot, 4); add(P * ktot, 4); add(S, 8); add(S, 8);

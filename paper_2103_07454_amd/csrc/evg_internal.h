@@ -9,6 +9,8 @@ constexpr int kThreads = 256;          // 4 wavefronts of 64 lanes
 constexpr int kLaneElems = 4;          // one float4 per lane and sweep
 constexpr int kSweep = kThreads * kLaneElems;   // elements one workgroup covers per sweep
 constexpr int kHistBins = 2048;        // 11 key bits per selection pass (passes A, B); pass C uses 512
+constexpr uint32_t kStageCap = 2048;   // staged entries / in-bin keys of a chunk that the staging kernel
+constexpr uint32_t kStageCapBin = 1024;   // gathers in LDS before writing them out (more: direct stores)
 
 // A chunk is a run of one tensor's elements that one workgroup handles; it never
 // straddles tensors, starts at a multiple of 4 elements and is at most chunk_elems long.
@@ -60,9 +62,11 @@ struct Tables {
   uint32_t* work_full; uint32_t* work_topk;   // [P*C] compact chunk lists (r*C + c)
   uint32_t* hist;          // [S*kHistBins]
   uint32_t* sel_prefix; uint32_t* sel_krem;   // [S]
-  uint32_t* stage_n;       // [P*C] staged entries per chunk (keys in or above the threshold bin)
-  uint32_t* stage_key; uint32_t* stage_idx; float* stage_val;   // [P*Npad], a chunk's entries
-                           // start at the chunk's arena offset, in ascending index order
+  uint2* stage_n;          // [P*C] per chunk: staged entries (bin >= the threshold bin), and how many
+                           // of them lie IN the threshold bin
+  uint32_t* stage_idx; float* stage_val;   // [P*Npad] a chunk's staged entries start at the chunk's arena
+                           // offset, in ascending index order; bit 31 of the index = in the threshold bin
+  uint32_t* stage_key;     // [P*Npad] the keys of the chunk's in-bin entries, same place, same order
   uint2* chunk_cnt;        // [P*C] (keys above threshold, keys equal) per chunk
   uint2* chunk_before;     // [P*C] the same, summed over the tensor's earlier chunks
   uint32_t* chunk_sub;     // [P*C*(SW+1)] winners before each 1024-element sweep of a chunk,

@@ -8,13 +8,15 @@
 //                 tensor's histogram with integer atomics; k_topk_pick<0> then finds
 //                 the bin b that holds the K-th largest key.
 //   k_topk_stage  copies every element whose bin is >= b ("staged": all possible
-//                 winners, roughly K plus one bin's worth) as (key, index, value) into
-//                 the chunk's staging slot in ascending index order, and histograms
-//                 bits 19..9 of the keys inside bin b.
+//                 winners, roughly K plus one bin's worth) as (index, value) into
+//                 the chunk's staging slot in ascending index order, marks those IN bin b
+//                 (bit 31 of the index), keeps the keys of the marked ones in a list of
+//                 their own, and histograms bits 19..9 of those keys.  Entries above bin b
+//                 win whatever the exact threshold turns out to be, so their keys are dropped.
 // The rest works on the staged entries only, a small fraction of the tensor:
-//   k_topk_hist_low   bits 8..0 of staged keys under the 22-bit prefix -> threshold key t
+//   k_topk_hist_low   bits 8..0 of the in-bin keys under the 22-bit prefix -> threshold key t
 //                     and T = how many keys equal to t are still needed
-//   k_topk_count      per chunk: staged keys > t and == t
+//   k_topk_count      per chunk: staged entries above bin b + in-bin keys > t, and in-bin keys == t
 //   k_topk_chunkscan  running totals over a tensor's chunks (one wavefront per tensor)
 //   k_topk_pack       stable compaction of the winners (key > t, or key == t while fewer
 //                     than T equal keys precede it in the tensor) into the tensor's
@@ -124,6 +126,12 @@ __global__ __launch_bounds__(kThreads) void k_topk_pick(Tables T) {
 // loads are in flight between barriers: the four per-sweep counts travel as 16-bit
 // fields of one 64-bit word (a sweep stages at most 1024 entries).  The entries are
 // compacted in LDS and written out once per chunk.
+//
+// What is staged per chunk, both lists in ascending index order at the chunk's arena offset:
+//   (index | in-bin flag in bit 31, value)  for every element whose bin is >= b: all possible winners;
+//   key                                     for those of them whose bin IS b (flag set): only they
+//                                           still have to be compared with the exact threshold,
+//                                           everything above bin b wins whatever the threshold is.
 template <int SWEEPS>
 __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
   constexpr int STEP = SWEEPS >= 4 ? 4 : SWEEPS;
@@ -131,9 +139,9 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
   __shared__ uint64_t ws[4];
   // a chunk's staged entries are gathered here and leave as whole 16-byte streaming stores
   // (scattered 4-byte stores straight to memory measured 12 % slower for the kernel); a chunk
-  // that stages more than the buffer holds falls back to direct stores
-  constexpr uint32_t kCap = 2048;
-  __shared__ __attribute__((aligned(16))) uint32_t lk[kCap], li[kCap];
+  // that stages more than the buffers hold falls back to direct stores
+  constexpr uint32_t kCap = kStageCap, kCapB = kStageCapBin;
+  __shared__ __attribute__((aligned(16))) uint32_t li[kCap], lb[kCapB];
   __shared__ __attribute__((aligned(16))) float lv[kCap];
   const uint32_t n = T.counts[1];
   for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
@@ -141,11 +149,11 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
     const uint32_t bin = T.sel_prefix[wi.seg];
     for (uint32_t b = threadIdx.x; b < (uint32_t)kHistBins; b += kThreads) h[b] = 0;
     __syncthreads();
-    uint32_t run = 0;
-    bool direct = false;     // uniform: this chunk overflowed the buffer
+    uint32_t run = 0, runb = 0;   // staged so far: all entries, in-bin entries
+    bool direct = false;          // uniform: this chunk overflowed a buffer
     for (int it = 0; it < SWEEPS; it += STEP) {   // uniform trip count: the scan needs every thread
       float xa[STEP][4];
-      uint32_t key[STEP][4], take[STEP], e[STEP];
+      uint32_t key[STEP][4], take[STEP], inb[STEP], e[STEP];
       float4 x4[STEP], h4[STEP];
 #pragma unroll
       for (int u = 0; u < STEP; ++u) {
@@ -157,10 +165,11 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
           if (!A.topk_key) h4[u] = ld4s(T.xhat + wi.base + e[u]);
         }
       }
-      uint64_t mine = 0;
+      uint64_t mine = 0, mineb = 0;
 #pragma unroll
       for (int u = 0; u < STEP; ++u) {
         take[u] = 0;
+        inb[u] = 0;
         xa[u][0] = x4[u].x; xa[u][1] = x4[u].y; xa[u][2] = x4[u].z; xa[u][3] = x4[u].w;
         const float ha[4] = {h4[u].x, h4[u].y, h4[u].z, h4[u].w};
         const uint32_t nv = e[u] >= wi.cd.len ? 0u : (wi.cd.len - e[u] < 4u ? wi.cd.len - e[u] : 4u);
@@ -171,68 +180,83 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
             key[u][q] = rank_key(xa[u][q], ha[q], A.topk_key);
             const uint32_t kb = key[u][q] >> 20;
             if (kb >= bin) take[u] |= 1u << q;
-            if (kb == bin) atomicAdd(&h[(key[u][q] >> 9) & 2047u], 1u);
+            if (kb == bin) {
+              inb[u] |= 1u << q;
+              atomicAdd(&h[(key[u][q] >> 9) & 2047u], 1u);
+            }
           }
         }
         mine |= (uint64_t)__popc(take[u]) << (16 * u);
+        mineb |= (uint64_t)__popc(inb[u]) << (16 * u);
       }
       // staged order = index order: all of sweep `it` precedes sweep `it + 1`
-      uint64_t total;
+      uint64_t total, totalb;
       const uint64_t ex = block_excl_scan64<4>(mine, ws, &total);
-      uint32_t before = run;            // entries of this chunk's earlier sweeps
-      uint32_t all = 0;
+      const uint64_t exb = block_excl_scan64<4>(mineb, ws, &totalb);
+      uint32_t before = run, beforeb = runb;   // entries of this chunk's earlier sweeps
+      uint32_t all = 0, allb = 0;
 #pragma unroll
-      for (int u = 0; u < STEP; ++u) all += (uint32_t)((total >> (16 * u)) & 0xFFFFu);
-      if (!direct && run + all > kCap) {       // uniform: does not fit, empty the buffer and go direct
+      for (int u = 0; u < STEP; ++u) {
+        all += (uint32_t)((total >> (16 * u)) & 0xFFFFu);
+        allb += (uint32_t)((totalb >> (16 * u)) & 0xFFFFu);
+      }
+      if (!direct && (run + all > kCap || runb + allb > kCapB)) {   // uniform: empty the buffers and go direct
         __syncthreads();
         for (uint32_t q = threadIdx.x; q < run; q += kThreads) {
-          T.stage_key[wi.base + q] = lk[q];
           T.stage_idx[wi.base + q] = li[q];
           T.stage_val[wi.base + q] = lv[q];
         }
+        for (uint32_t q = threadIdx.x; q < runb; q += kThreads) T.stage_key[wi.base + q] = lb[q];
         direct = true;
       }
 #pragma unroll
       for (int u = 0; u < STEP; ++u) {
         uint32_t pos = before + (uint32_t)((ex >> (16 * u)) & 0xFFFFu);
+        uint32_t posb = beforeb + (uint32_t)((exb >> (16 * u)) & 0xFFFFu);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           if ((take[u] >> q) & 1u) {
+            const uint32_t flag = (inb[u] >> q) & 1u;
+            const uint32_t jf = (wi.cd.j0 + e[u] + q) | (flag << 31);
             if (!direct) {
-              lk[pos] = key[u][q];
-              li[pos] = wi.cd.j0 + e[u] + q;
+              li[pos] = jf;
               lv[pos] = xa[u][q];
+              if (flag) lb[posb] = key[u][q];
             } else {
-              T.stage_key[wi.base + pos] = key[u][q];
-              T.stage_idx[wi.base + pos] = wi.cd.j0 + e[u] + q;
+              T.stage_idx[wi.base + pos] = jf;
               T.stage_val[wi.base + pos] = xa[u][q];
+              if (flag) T.stage_key[wi.base + posb] = key[u][q];
             }
             ++pos;
+            posb += flag;
           }
         }
         before += (uint32_t)((total >> (16 * u)) & 0xFFFFu);
+        beforeb += (uint32_t)((totalb >> (16 * u)) & 0xFFFFu);
       }
       run = before;
+      runb = beforeb;
     }
-    if (threadIdx.x == 0) T.stage_n[wi.w] = run;
+    if (threadIdx.x == 0) T.stage_n[wi.w] = make_uint2(run, runb);
     __syncthreads();
     if (!direct) {
       // the chunk's slot starts 16-byte aligned: whole quads stream out, the tail goes singly
-      const uint32_t quads = run / 4;
+      typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+      const uint32_t quads = run / 4, quadsb = runb / 4;
       for (uint32_t q = threadIdx.x; q < quads; q += kThreads) {
-        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-        __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(lk + 4 * q),
-                                    reinterpret_cast<u32x4*>(T.stage_key + wi.base) + q);
         __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(li + 4 * q),
                                     reinterpret_cast<u32x4*>(T.stage_idx + wi.base) + q);
         __builtin_nontemporal_store(*reinterpret_cast<const f32x4*>(lv + 4 * q),
                                     reinterpret_cast<f32x4*>(T.stage_val + wi.base) + q);
       }
+      for (uint32_t q = threadIdx.x; q < quadsb; q += kThreads)
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(lb + 4 * q),
+                                    reinterpret_cast<u32x4*>(T.stage_key + wi.base) + q);
       for (uint32_t q = 4 * quads + threadIdx.x; q < run; q += kThreads) {
-        T.stage_key[wi.base + q] = lk[q];
         T.stage_idx[wi.base + q] = li[q];
         T.stage_val[wi.base + q] = lv[q];
       }
+      for (uint32_t q = 4 * quadsb + threadIdx.x; q < runb; q += kThreads) T.stage_key[wi.base + q] = lb[q];
     }
 
     flush_hist<kHistBins>(h, T.hist + (size_t)wi.seg * kHistBins);
@@ -240,7 +264,7 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
   }
 }
 
-// The three kernels below walk a chunk's staged entries, a few hundred at most, so
+// The three kernels below walk a chunk's staged entries, a thousand or so, so
 // one wavefront per chunk does it without LDS or workgroup barriers: ballots give
 // counts and ranks.  Four independent wavefronts share a workgroup.
 
@@ -268,14 +292,14 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
 
 constexpr int kBatch = 8;    // 64-entry groups loaded together by a wavefront, to overlap their latency
 
-// Bits 8..0 of the staged keys that carry the 22-bit prefix found so far.  Matches are
+// Bits 8..0 of the in-bin keys that carry the 22-bit prefix found so far.  Matches are
 // rare (a 2^-22 slice of the key range), so they go straight to the tensor's histogram,
 // one atomic per distinct value per 64 entries.
 __global__ __launch_bounds__(kThreads) void k_topk_hist_low(Tables T) {
   const uint32_t n = T.counts[1];
   for (uint32_t i = wave_slot(); i < n; i += wave_slots()) {
     const WorkItem wi = work_item(T, i);
-    const uint32_t prefix = T.sel_prefix[wi.seg], ns = T.stage_n[wi.w];
+    const uint32_t prefix = T.sel_prefix[wi.seg], ns = T.stage_n[wi.w].y;
     uint32_t* gh = T.hist + (size_t)wi.seg * kHistBins;
     for (uint32_t q0 = 0; q0 < ns; q0 += 64 * kBatch) {
       uint32_t key[kBatch];
@@ -302,13 +326,16 @@ __global__ __launch_bounds__(kThreads) void k_topk_hist_low(Tables T) {
 }
 
 // Per chunk: how many staged keys exceed / equal the threshold key.  Every key above
-// the threshold is staged (its bin is >= the threshold's), so these are the chunk's counts.
+// the threshold is staged (its bin is >= the threshold's), so these are the chunk's counts;
+// entries staged without a key lie above the threshold's bin and exceed it.
 __global__ __launch_bounds__(kThreads) void k_topk_count(Tables T) {
   const uint32_t n = T.counts[1];
   for (uint32_t i = wave_slot(); i < n; i += wave_slots()) {
     const WorkItem wi = work_item(T, i);
-    const uint32_t t = T.sel_prefix[wi.seg], ns = T.stage_n[wi.w];
-    uint32_t g = 0, e = 0;
+    const uint32_t t = T.sel_prefix[wi.seg];
+    const uint2 sn = T.stage_n[wi.w];
+    const uint32_t ns = sn.y;
+    uint32_t g = sn.x - sn.y, e = 0;
     for (uint32_t q0 = 0; q0 < ns; q0 += 64 * kBatch) {
       uint32_t key[kBatch];
       bool in[kBatch];
@@ -355,25 +382,36 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
   const uint32_t n = T.counts[1];
   for (uint32_t i = wave_slot(); i < n; i += wave_slots()) {
     const WorkItem wi = work_item(T, i);
-    const uint32_t t = T.sel_prefix[wi.seg], ties = T.sel_krem[wi.seg], ns = T.stage_n[wi.w];
+    const uint32_t t = T.sel_prefix[wi.seg], ties = T.sel_krem[wi.seg], ns = T.stage_n[wi.w].x;
     const uint2 before = T.chunk_before[wi.w];
     const size_t mbase = (size_t)wi.r * T.Ktot + T.layers[wi.cd.layer].msg_off;
     uint32_t* sub = T.chunk_sub + (size_t)wi.w * (T.SW + 1);
     const uint32_t first = before.x + (before.y < ties ? before.y : ties);   // the chunk's first slot
     uint32_t run_g = before.x, run_e = before.y;
+    uint32_t run_b = 0;                                 // in-bin entries of this chunk met so far
     uint32_t per_sweep[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // winners per sweep (wave-uniform)
     unsigned long long hi = 0ull, hm = 0ull;            // this lane's share of the fingerprints
     for (uint32_t q0 = 0; q0 < ns; q0 += 64 * kBatch) {
       uint32_t key[kBatch], j[kBatch];
       float val[kBatch];
-      bool in[kBatch];
+      bool in[kBatch], flag[kBatch];
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const uint32_t q = q0 + u * 64 + lane_id();
         in[u] = q < ns;
-        key[u] = in[u] ? T.stage_key[wi.base + q] : 0u;
         j[u] = in[u] ? T.stage_idx[wi.base + q] : wi.cd.j0;
-        val[u] = in[u] ? T.stage_val[wi.base + q] : 0.0f;   // most staged entries win: fetch with the keys
+        val[u] = in[u] ? T.stage_val[wi.base + q] : 0.0f;   // most staged entries win: fetch with the indices
+      }
+      // an entry with the in-bin flag finds its key in the chunk's key list, at its rank among
+      // the flagged entries; the others lie above the threshold's bin (any key above t will do)
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        flag[u] = (j[u] >> 31) != 0u;
+        j[u] &= 0x7FFFFFFFu;
+        const uint64_t mf = __ballot(flag[u]);
+        key[u] = 0xFFFFFFFFu;
+        if (flag[u]) key[u] = T.stage_key[wi.base + run_b + lanes_below(mf)];
+        run_b += __popcll(mf);
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {                // groups in index order
