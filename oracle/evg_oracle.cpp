@@ -39,12 +39,14 @@
 //   R9  delivery_delay = 1 is a deterministic stand-in for the asynchrony of one-sided
 //       puts (Section 7 blames it for threshold oscillations): what is sent in iteration
 //       k is written into the neighbours' memory only after iteration k's updates.
-//   R10 xhat_reset = 1 is the other reading of "previously communicated values" after a
+//   R10 xhat_reset = 1 is the other reading of what xhat holds after a
 //       Top-K event (Section 4 defines xhat per tensor, Section 7 sends only part of it):
 //       the whole tensor's xhat becomes x, as after a whole send, while the receivers'
 //       copies still change only at the sent indices.
 //   R8  gradients are synthetic: a counter-based Philox4x32-10 stream turned
-//       into normals by Box-Muller with fixed polynomial log/sin/cos.
+//       into normals by Box-Muller with fixed polynomial log/sin/cos; Student-t(3)
+//       variates take three uniforms each (one Box-Muller pair and the squared radius
+//       of a second one), four variates per three Philox blocks.
 //
 // parity unpinned: R6's choice of key and of which xhat entries reset cannot be
 // checked against the authors' code (not available); everything else is pinned
@@ -234,15 +236,28 @@ struct Oracle {
         for (uint64_t i = 0; i < 4 && j0 + i < n; ++i) g[j0 + i] = sg * z[i];
       }
     } else {
-      for (uint64_t j = 0; j < n; ++j) {
-        const uint32_t ctr[4] = {(uint32_t)j, l, (uint32_t)k, r};
-        uint32_t w[4];
-        float z[4];
-        philox4x32_10(ctr, key, w);
-        normal4(w, z);
-        const float q = std::fmaf(z[3], z[3], std::fmaf(z[2], z[2], z[1] * z[1]));
-        const float t = z[0] * std::sqrt(3.0f / q);
-        g[j] = sg * t;
+      // Student-t with 3 degrees of freedom, t = z0 / sqrt(chi2_3 / 3) with chi2_3 = z1^2 + E:
+      // (z0, z1) is one Box-Muller pair and E = -2 ln u is the squared radius of a second,
+      // independent pair (a chi-square with 2 degrees of freedom), so three uniforms make one
+      // variate.  Elements 4g .. 4g+3 share the three Philox blocks 3g, 3g+1, 3g+2 of the
+      // (tensor, iteration, worker) stream: element 4g+i takes words 3i, 3i+1, 3i+2 of the twelve.
+      for (uint64_t j0 = 0; j0 < n; j0 += 4) {
+        uint32_t w[12];
+        for (uint32_t b = 0; b < 3; ++b) {
+          const uint32_t ctr[4] = {(uint32_t)(3 * (j0 >> 2) + b), l, (uint32_t)k, r};
+          philox4x32_10(ctr, key, w + 4 * b);
+        }
+        for (uint64_t i = 0; i < 4 && j0 + i < n; ++i) {
+          const float ua = uniform01(w[3 * i]), ub = uniform01(w[3 * i + 1]), uc = uniform01(w[3 * i + 2]);
+          const float rad = std::sqrt(-2.0f * log_poly(ua));
+          float c, s;
+          sincos2pi_poly(ub, &c, &s);
+          const float z0 = rad * c, z1 = rad * s;
+          const float e2 = -2.0f * log_poly(uc);
+          const float q = std::fmaf(z1, z1, e2);
+          const float t = z0 * std::sqrt(3.0f / q);
+          g[j0 + i] = sg * t;
+        }
       }
     }
     if (sp) for (uint64_t j = 0; j < n; ++j) g[j] = g[j] * cfg.spike_gain;

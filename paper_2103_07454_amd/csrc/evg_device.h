@@ -203,10 +203,17 @@ __device__ __forceinline__ void normals4(const Rand4& r, float z[4]) {
   }
 }
 
-// Student-t with 3 degrees of freedom from four normals.
-__device__ __forceinline__ float student_t3(const float z[4]) {
-  const float q = __builtin_fmaf(z[3], z[3], __builtin_fmaf(z[2], z[2], z[1] * z[1]));
-  return z[0] * __builtin_sqrtf(3.0f / q);
+// Student-t with 3 degrees of freedom from three random words: t = z0 / sqrt((z1^2 + E) / 3),
+// where (z0, z1) is the Box-Muller pair of words (a, b) and E = -2 ln u(c) is a chi-square with
+// two degrees of freedom (the squared radius of a second, independent pair).
+__device__ __forceinline__ float student_t3(uint32_t wa, uint32_t wb, uint32_t wc) {
+  const float rad = __builtin_sqrtf(-2.0f * ln_series(unit_open(wa)));
+  float c, s;
+  turn_cos_sin(unit_open(wb), c, s);
+  const float z0 = rad * c, z1 = rad * s;
+  const float e2 = -2.0f * ln_series(unit_open(wc));
+  const float q = __builtin_fmaf(z1, z1, e2);
+  return z0 * __builtin_sqrtf(3.0f / q);
 }
 
 // Key that ranks elements for Top-K: the bit pattern of a non-negative float is

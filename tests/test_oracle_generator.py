@@ -1,6 +1,6 @@
 """Pins for the oracle's synthetic-gradient generator (CPU only).
 
-The generator replaces Alg. B's "compute the local stochastic gradient" step
+The generator stands in for the gradient computation step of Alg. B
 with a counter-based stream, so it is pinned against things other than itself:
 published known-answer vectors, an independent big-integer transcription of the
 published round function, libm, and distribution tests against scipy.
@@ -115,11 +115,21 @@ def test_counter_layout(oracle_mod):
         for j in range(g.size):
             z = oracle_mod.normal4(philox_bigint([j // 4, l, k, r], key))
             assert g[j] == z[j % 4]
+    # Student-t(3): elements 4g .. 4g+3 share Philox blocks 3g, 3g+1, 3g+2; element 4g+i takes words
+    # 3i (radius of its normal pair), 3i+1 (angle), 3i+2 (the chi-square(2) part of the denominator)
     ot = _orc(oracle_mod, tensors, P=4, seed=seed, sigma0=1.0, dist=1)
-    g = ot.grad_tensor(2, 9, 0)
-    for j in range(g.size):
-        z = oracle_mod.normal4(philox_bigint([j, 0, 9, 2], key)).astype(np.float64)
-        assert abs(g[j] - z[0] * math.sqrt(3 / (z[1]**2 + z[2]**2 + z[3]**2))) < 1e-5 * max(1, abs(g[j]))
+    for (r, k, l) in [(2, 9, 0), (0, 0, 1), (3, 4, 2)]:
+        g = ot.grad_tensor(r, k, l)
+        for j in range(g.size):
+            words = []
+            for b in range(3):
+                words += philox_bigint([3 * (j // 4) + b, l, k, r], key)
+            i = j % 4
+            ua, ub, uc = (((w >> 9) + 0.5) / 2**23 for w in words[3 * i:3 * i + 3])
+            rad = math.sqrt(-2 * math.log(ua))
+            z0, z1 = rad * math.cos(2 * math.pi * ub), rad * math.sin(2 * math.pi * ub)
+            want = z0 * math.sqrt(3 / (z1 * z1 - 2 * math.log(uc)))
+            assert abs(g[j] - want) < 1e-5 * max(1, abs(want)), (r, k, l, j)
 
 
 def test_normal_distribution(oracle_mod):
@@ -142,6 +152,12 @@ def test_student_t_distribution(oracle_mod):
     g = o.grad_tensor(0, 0, 0).astype(np.float64)
     assert stats.kstest(g, "t", args=(3,)).pvalue > 1e-3
     assert abs(np.quantile(g, 0.75) - stats.t.ppf(0.75, 3)) < 0.01   # ~0.765
+    assert abs(np.quantile(g, 0.99) - stats.t.ppf(0.99, 3)) < 0.15   # ~4.54: the heavy tail is there
+    assert abs(np.median(g)) < 0.01
+    # variates that share Philox blocks are uncorrelated (signs and magnitudes)
+    for a, b in ((g[0::4], g[1::4]), (g[1::4], g[2::4]), (g[:-4:4], g[4::4])):
+        assert abs(np.corrcoef(np.sign(a), np.sign(b))[0, 1]) < 0.02
+        assert abs(stats.spearmanr(np.abs(a), np.abs(b)).statistic) < 0.02
 
 
 def test_sigma_fan_in_decay_and_spike(oracle_mod):

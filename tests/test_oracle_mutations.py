@@ -59,6 +59,9 @@ MUTANTS = [
     ("spike_counter_moved", "{0u, 0xFFFFFFFFu, (uint32_t)k, r}", "{0u, 0xFFFFFFFEu, (uint32_t)k, r}"),
     ("spike_draw_from_other_word", "return uniform01(w[0]) < cfg.spike_prob;", "return uniform01(w[1]) < cfg.spike_prob;"),
     ("student_t_degrees", "std::sqrt(3.0f / q)", "std::sqrt(2.0f / q)"),
+    ("student_t_denominator_reuses_the_angle_word", "uc = uniform01(w[3 * i + 2]);", "uc = uniform01(w[3 * i + 1]);"),
+    ("student_t_blocks_overlap", "(uint32_t)(3 * (j0 >> 2) + b)", "(uint32_t)((j0 >> 2) + b)"),
+    ("student_t_chi_square_without_the_normal_term", "std::fmaf(z1, z1, e2)", "e2"),
     # delayed delivery and the other reading of a Top-K event
     ("delayed_messages_land_at_once", "const bool now = c.delivery_delay == 0;", "const bool now = true;"),
     ("xhat_reset_ignored", "if (c.xhat_reset)\n", "if (false)\n"),
