@@ -150,6 +150,10 @@ typedef struct {
   uint64_t regular_words;   /* P * N * iters                                     */
   uint64_t near_tie_flags;  /* tests with |norm - delta| < 1e-6 * delta          */
   uint64_t nonfinite_norms; /* tests whose norm was NaN or infinite              */
+  uint64_t library_bytes;   /* device memory the library holds for this context besides the
+                               caller's five arenas (tables, work lists, Top-K histograms,
+                               staging and message buffers); for evg_init_static the part
+                               of the static block in use                           */
   /* optional per-(worker, tensor) outputs, HOST arrays of P*L entries or NULL  */
   uint32_t* events_full_rl;
   uint32_t* events_topk_rl;

@@ -83,6 +83,7 @@ struct evg_ctx {
   unsigned char* arena_base = nullptr;   // null = tables come from hipMalloc
   size_t arena_used = 0;
   int arena_dev = -1;
+  uint64_t owned_bytes = 0;              // device memory handed out by dalloc
   // timing
   bool timing = false;
   std::vector<TimerPair> pending;
@@ -106,6 +107,7 @@ struct evg_ctx {
       if (e != hipSuccess) return fail(EVG_ERR_OOM, "hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(e));
       owned.push_back(d);
     }
+    owned_bytes += bytes;
     if (zero) HIP_TRY(hipMemsetAsync(d, 0, bytes, stream));
     *p = static_cast<T*>(d);
     return EVG_OK;
@@ -714,6 +716,7 @@ evg_status evg_stats(evg_ctx* c, evg_stats_t* out) {
   out->regular_words = (uint64_t)t.P * c->N * c->iters;
   out->near_tie_flags = near;
   out->nonfinite_norms = nonf;
+  out->library_bytes = c->owned_bytes;
   return EVG_OK;
 }
 

@@ -154,18 +154,49 @@ def main():
         with open(os.path.join(a.out, f"hbm_traffic_pmc_{w.name}.md"), "w") as f:
             f.write("\n".join(out) + "\n")
 
-    # ---- VALU instructions ------------------------------------------------------------
+    # ---- SQ counters ------------------------------------------------------------------
     if a.valu:
-        insts = counter_rows(a.valu, "SQ_INSTS_VALU")
-        ku = [k for k in insts if "k_update" in k]
+        names = ["SQ_WAVES", "SQ_BUSY_CYCLES", "SQ_WAIT_INST_ANY", "SQ_ACTIVE_INST_VALU", "SQ_ACTIVE_INST_VMEM",
+                 "SQ_ACTIVE_INST_LDS", "SQ_LDS_BANK_CONFLICT", "SQ_INSTS_VALU"]
+        data = {n: counter_rows(a.valu, n) for n in names}
+        drop = a.valu_warmup + 2                      # warm-up launches and the all-fire iterations 0, 1
+
+        def avg(name, kernel):
+            v = data[name].get(kernel, [])
+            v = v[drop:] if len(v) > drop else v
+            return sum(v) / len(v) if v else float("nan")
+
+        sq_cmd = (f"rocprofv3 --pmc {' '.join(names)} --kernel-trace --output-format csv -d <out> -o cfg{c} -- "
+                  f"python3 <repo>/bench.py --config {c} --steps {a.valu_steps} --warmup {a.valu_warmup} "
+                  f"--no-cpu-baseline --no-phase-timers")
+        out = [f"# SQ counters of the per-step kernels (rocprofv3 --pmc), configuration {c} ({w.name})", "",
+               "Command (on the MI355X box, after `cd /tmp && export TMPDIR=/tmp`):", "", f"    {sq_cmd}", "",
+               f"Averages per launch over iterations 2..{a.valu_steps - 1} (the all-fire iterations 0 and 1 dropped). The counters are sums",
+               "over the chip's shader engines; they are given as ratios to SQ_BUSY_CYCLES of the same launch, which makes",
+               "launches of different length comparable but is not a utilisation in percent (the counters' units differ).", "",
+               "| kernel | waves | VALU-active / busy | VMEM-active / busy | LDS-active / busy | wait-any / busy | LDS bank conflict / busy | VALU wave-instructions |",
+               "|---|---|---|---|---|---|---|---|"]
+        for k in data["SQ_WAVES"]:
+            if "evg::" not in k or avg("SQ_WAVES", k) < 1000:
+                continue
+            busy = avg("SQ_BUSY_CYCLES", k)
+            out.append(f"| {short(k)} | {avg('SQ_WAVES', k):.0f} | {avg('SQ_ACTIVE_INST_VALU', k) / busy:.2f} | "
+                       f"{avg('SQ_ACTIVE_INST_VMEM', k) / busy:.2f} | {avg('SQ_ACTIVE_INST_LDS', k) / busy:.2f} | "
+                       f"{avg('SQ_WAIT_INST_ANY', k) / busy:.1f} | {avg('SQ_LDS_BANK_CONFLICT', k) / busy:.3f} | "
+                       f"{avg('SQ_INSTS_VALU', k):.3g} |")
+        ku = [k for k in data["SQ_INSTS_VALU"] if "k_update" in k]
         if ku:
-            v = insts[ku[0]]
-            v = v[a.valu_warmup + 2:] if len(v) > a.valu_warmup + 2 else v      # all-fire iterations 0, 1 dropped too
-            per_launch = sum(v) / len(v)
+            per_launch = avg("SQ_INSTS_VALU", ku[0])
+            per_elem = per_launch * 64 / elems
+            alu_ms = per_launch * 4 / 1024 / 2.4e9 * 1e3
             record["kernels"].setdefault("k_update", {}).update(
-                valu_wave_instructions_per_launch=per_launch, valu_instructions_per_element=per_launch * 64 / elems,
-                valu_command=f"rocprofv3 --pmc SQ_INSTS_VALU ... -- python3 <repo>/bench.py --config {c} --steps {a.valu_steps} "
-                             f"--warmup {a.valu_warmup} --no-cpu-baseline --no-phase-timers")
+                valu_wave_instructions_per_launch=per_launch, valu_instructions_per_element=per_elem, valu_command=sq_cmd)
+            out += ["", "A 64-lane wavefront occupies its SIMD for at least 4 cycles per vector instruction, and the chip has 256 CUs x 4 SIMDs",
+                    f"at 2.4 GHz: the update pass executes {per_launch:.3g} wave-instructions per launch = {per_elem:.0f} per element, which the vector",
+                    f"ALUs alone need {alu_ms:.2f} ms for (quarter-rate instructions such as 32-bit integer multiplies take longer), against "
+                    f"{rf['avg_launch_ms']:.2f} ms per launch."]
+        with open(os.path.join(a.out, f"sq_counters_{w.name}.md"), "w") as f:
+            f.write("\n".join(out) + "\n")
     with open(os.path.join(a.out, f"counters_{w.name}.json"), "w") as f:
         json.dump(record, f, indent=1, sort_keys=True)
         f.write("\n")
