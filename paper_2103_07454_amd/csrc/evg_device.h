@@ -47,13 +47,17 @@ __device__ __forceinline__ double block_sum(double v, double* ws) {
   return total;
 }
 
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves, no LDS traffic:
+// shifted adds by 1, 2, 4, 8 inside each row of 16 lanes (lanes shifted in from outside a row
+// read 0), then the last lane of rows 0 and 2 is added to rows 1 and 3, and lane 31 (by then the
+// sum of rows 0-1) to rows 2 and 3.
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
-  const uint32_t lane = lane_id();
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t t = __shfl_up(v, o, 64);
-    if (lane >= (uint32_t)o) v += t;
-  }
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);   // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true);   // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);   // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true);   // row_shr:8
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, true);   // row_bcast:15 -> rows 1, 3
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, true);   // row_bcast:31 -> rows 2, 3
   return v;
 }
 
@@ -76,28 +80,29 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* ws, ui
   return before + incl - v;
 }
 
-// The same over 64-bit words (several small counters packed into one).
+// The same over 64-bit words that pack four 16-bit counters none of which can overflow its
+// field (so the two 32-bit halves scan independently), two such words at once: one barrier pair
+// serves both.  `ws` is 2 * W uint64 of LDS.
 template <int W>
-__device__ __forceinline__ uint64_t block_excl_scan64(uint64_t v, uint64_t* ws, uint64_t* total) {
-  const uint32_t lane = lane_id();
-  uint64_t incl = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint64_t t = __shfl_up((unsigned long long)incl, o, 64);
-    if (lane >= (uint32_t)o) incl += t;
-  }
-  if (lane == 63) ws[wave_id()] = incl;
+__device__ __forceinline__ void block_excl_scan64x2(uint64_t a, uint64_t b, uint64_t* ws, uint64_t* ex_a,
+                                                    uint64_t* ex_b, uint64_t* total_a, uint64_t* total_b) {
+  const uint64_t ia = ((uint64_t)wave_incl_scan((uint32_t)(a >> 32)) << 32) | wave_incl_scan((uint32_t)a);
+  const uint64_t ib = ((uint64_t)wave_incl_scan((uint32_t)(b >> 32)) << 32) | wave_incl_scan((uint32_t)b);
+  if (lane_id() == 63) { ws[wave_id()] = ia; ws[W + wave_id()] = ib; }
   __syncthreads();
-  uint64_t before = 0, all = 0;
+  uint64_t before_a = 0, all_a = 0, before_b = 0, all_b = 0;
 #pragma unroll
   for (int w = 0; w < W; ++w) {
-    const uint64_t s = ws[w];
-    if ((uint32_t)w < wave_id()) before += s;
-    all += s;
+    const uint64_t sa = ws[w], sb = ws[W + w];
+    if ((uint32_t)w < wave_id()) { before_a += sa; before_b += sb; }
+    all_a += sa;
+    all_b += sb;
   }
   __syncthreads();
-  *total = all;
-  return before + incl - v;
+  *total_a = all_a;
+  *total_b = all_b;
+  *ex_a = before_a + ia - a;
+  *ex_b = before_b + ib - b;
 }
 
 // The same accesses with the choice left to the caller: a ring whose arenas fit the

@@ -136,7 +136,7 @@ template <int SWEEPS>
 __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
   constexpr int STEP = SWEEPS >= 4 ? 4 : SWEEPS;
   __shared__ uint32_t h[kHistBins];
-  __shared__ uint64_t ws[4];
+  __shared__ uint64_t ws[8];
   // a chunk's staged entries are gathered here and leave as whole 16-byte streaming stores
   // (scattered 4-byte stores straight to memory measured 12 % slower for the kernel); a chunk
   // that stages more than the buffers hold falls back to direct stores
@@ -190,9 +190,8 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
         mineb |= (uint64_t)__popc(inb[u]) << (16 * u);
       }
       // staged order = index order: all of sweep `it` precedes sweep `it + 1`
-      uint64_t total, totalb;
-      const uint64_t ex = block_excl_scan64<4>(mine, ws, &total);
-      const uint64_t exb = block_excl_scan64<4>(mineb, ws, &totalb);
+      uint64_t total, totalb, ex, exb;
+      block_excl_scan64x2<4>(mine, mineb, ws, &ex, &exb, &total, &totalb);
       uint32_t before = run, beforeb = runb;   // entries of this chunk's earlier sweeps
       uint32_t all = 0, allb = 0;
 #pragma unroll
