@@ -220,6 +220,7 @@ def main():
                    "communication_pct_of_regular":
                        100.0 * (st["value_words"] + st["index_words"]) / max(1, st["regular_words"])},
         "library_owned_bytes": st["library_bytes"],
+        "topk_chunks_not_staged": st["chunks_not_staged"],
         "step_algorithmic_bytes_per_element": step_bytes_per_elem,
         "step_achieved_GBps": step_bytes_per_elem * elems * args.steps / dt / 1e9,
         "step_frac_of_hbm_peak": step_bytes_per_elem * elems * args.steps / dt / 1e9 / HBM_PEAK_GBS,

@@ -150,6 +150,9 @@ typedef struct {
   uint64_t regular_words;   /* P * N * iters                                     */
   uint64_t near_tie_flags;  /* tests with |norm - delta| < 1e-6 * delta          */
   uint64_t nonfinite_norms; /* tests whose norm was NaN or infinite              */
+  uint64_t chunks_not_staged; /* Top-K work granules whose possible winners exceeded their staging
+                               slot and were selected straight from x and xhat instead (slower,
+                               same result): massive ties or winners crowded into a few granules */
   uint64_t library_bytes;   /* device memory the library holds for this context besides the
                                caller's five arenas (tables, work lists, Top-K histograms,
                                staging and message buffers); for evg_init_static the part

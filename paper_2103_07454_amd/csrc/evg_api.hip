@@ -256,8 +256,17 @@ evg_status evg_destroy(evg_ctx* c) {
 
 // Bytes of library-owned device tables a configuration needs, with every table rounded up to
 // the scratch block's alignment: the same list as the allocations of init_common.
+// Staging entries reserved per 16 elements of a chunk.  The possible winners of a Top-K event are
+// its K winners plus the rest of the threshold bin (a 9 % wide slice of the key range: a few per
+// cent of the tensor): one and a half times the Top-K share plus a sixteenth covers that with room
+// to spare, and a chunk that needs more is handled from the arenas.
+static uint32_t stage_num_for(uint32_t topk_ppm) {
+  const uint64_t want = (3ull * topk_ppm * 8ull + 999999ull) / 1000000ull + 1ull;   // in sixteenths
+  return want <= 4 ? 4u : want <= 8 ? 8u : want <= 12 ? 12u : 16u;
+}
+
 static uint64_t table_bytes(uint64_t P, uint64_t L, uint64_t C, uint64_t SW, uint64_t hist_len, uint64_t Npad,
-                            uint64_t ktot, bool topk, bool norm_diff) {
+                            uint64_t ktot, uint64_t stage_num, bool topk, bool norm_diff) {
   const uint64_t S = P * L, PC = P * C;
   uint64_t total = 0;
   auto add = [&total](uint64_t count, uint64_t elem) {
@@ -274,7 +283,8 @@ static uint64_t table_bytes(uint64_t P, uint64_t L, uint64_t C, uint64_t SW, uin
   add(PC, 4);                                            // work_full
   if (topk) {
     add(PC, 4); add(S * kHistBins, 4); add(S, 4); add(S, 4); add(PC, 8);
-    add(P * Npad, 4); add(P * Npad, 4); add(P * Npad, 4);
+    const uint64_t stage = P * (Npad / 16 * stage_num);
+    add(stage, 4); add(stage, 4); add(stage, 4);
     add(PC, 8); add(PC, 8); add(PC * (SW + 1), 4);
     add(P * ktot, 4); add(P * ktot, 4); add(S, 8); add(S, 8);
   }
@@ -403,6 +413,8 @@ static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_st
   t.hist_len = cfg->thr_mode == EVG_THR_ADAPTIVE ? cfg->hist_len : 1;
   t.Ktot = (uint32_t)ktot;
   t.Npad = Npad;
+  t.stage_num = stage_num_for(cfg->topk_ppm);
+  t.stage_stride = Npad / 16 * t.stage_num;
   t.x = cfg->x; t.xhat = cfg->xhat; t.mbox_l = cfg->mbox_l; t.mbox_r = cfg->mbox_r; t.vel = cfg->vel;
   int dev = 0, cus = 256;
   ChunkDesc* d_chunks = nullptr;
@@ -426,7 +438,7 @@ static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_st
   HIP_OR_FREE(hipGetDevice(&dev));
   HIP_OR_FREE(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   if (use_scratch) {
-    const uint64_t need = table_bytes(P, L, C, t.SW, t.hist_len, Npad, ktot, cfg->topk_ppm != 0,
+    const uint64_t need = table_bytes(P, L, C, t.SW, t.hist_len, Npad, ktot, t.stage_num, cfg->topk_ppm != 0,
                                       cfg->trigger_kind == EVG_TRIGGER_NORM_DIFF);
     if (need > kScratchBytes) {
       evg_destroy(c);
@@ -508,9 +520,9 @@ static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_st
     TRY_OR_FREE(c->dalloc(&t.sel_prefix, S, true));
     TRY_OR_FREE(c->dalloc(&t.sel_krem, S, true));
     TRY_OR_FREE(c->dalloc(&t.stage_n, P * C, true));
-    TRY_OR_FREE(c->dalloc(&t.stage_key, (uint64_t)P * Npad, false));
-    TRY_OR_FREE(c->dalloc(&t.stage_idx, (uint64_t)P * Npad, false));
-    TRY_OR_FREE(c->dalloc(&t.stage_val, (uint64_t)P * Npad, false));
+    TRY_OR_FREE(c->dalloc(&t.stage_key, (uint64_t)P * t.stage_stride, false));
+    TRY_OR_FREE(c->dalloc(&t.stage_idx, (uint64_t)P * t.stage_stride, false));
+    TRY_OR_FREE(c->dalloc(&t.stage_val, (uint64_t)P * t.stage_stride, false));
     TRY_OR_FREE(c->dalloc(&t.chunk_cnt, P * C, true));
     TRY_OR_FREE(c->dalloc(&t.chunk_before, P * C, true));
     TRY_OR_FREE(c->dalloc(&t.chunk_sub, P * C * (t.SW + 1), true));
@@ -716,6 +728,9 @@ evg_status evg_stats(evg_ctx* c, evg_stats_t* out) {
   out->regular_words = (uint64_t)t.P * c->N * c->iters;
   out->near_tie_flags = near;
   out->nonfinite_norms = nonf;
+  uint32_t not_staged = 0;
+  HIP_TRY(hipMemcpy(&not_staged, t.counts + 3, 4, hipMemcpyDeviceToHost));
+  out->chunks_not_staged = not_staged;
   out->library_bytes = c->owned_bytes;
   return EVG_OK;
 }

@@ -58,15 +58,20 @@ struct Tables {
   uint32_t* ev_full; uint32_t* ev_topk; uint32_t* near_cnt; uint32_t* nonfinite_cnt;
   float* slope_hist; uint32_t* slope_cnt;   // [S*hist_len], [S]
   uint32_t* seg_woff_full; uint32_t* seg_woff_topk;   // [S] exclusive scans
-  uint32_t* counts;        // [0] chunks to copy whole, [1] chunks of Top-K tensors, [2] Top-K tensors
+  uint32_t* counts;        // [0] chunks to copy whole, [1] chunks of Top-K tensors, [2] Top-K tensors,
+                           // [3] chunks so far whose possible winners did not fit their staging slot
   uint32_t* work_full; uint32_t* work_topk;   // [P*C] compact chunk lists (r*C + c)
   uint32_t* hist;          // [S*kHistBins]
   uint32_t* sel_prefix; uint32_t* sel_krem;   // [S]
   uint2* stage_n;          // [P*C] per chunk: staged entries (bin >= the threshold bin), and how many
-                           // of them lie IN the threshold bin
-  uint32_t* stage_idx; float* stage_val;   // [P*Npad] a chunk's staged entries start at the chunk's arena
-                           // offset, in ascending index order; bit 31 of the index = in the threshold bin
-  uint32_t* stage_key;     // [P*Npad] the keys of the chunk's in-bin entries, same place, same order
+                           // of them lie IN the threshold bin; x = 0xFFFFFFFF: more than the chunk's
+                           // slot holds, nothing staged (its elements are then read from the arenas)
+  uint32_t* stage_idx; float* stage_val;   // [P*stage_stride] a chunk's staged entries, in ascending index
+                           // order; bit 31 of the index = in the threshold bin.  The chunk at arena
+                           // offset `off` owns entries (off/16)*stage_num .. +(len/16)*stage_num
+  uint32_t* stage_key;     // [P*stage_stride] the keys of the chunk's in-bin entries, same place, same order
+  uint32_t stage_num;      // staging entries per 16 elements: 4, 8, 12 or 16
+  uint64_t stage_stride;   // staging entries per worker
   uint2* chunk_cnt;        // [P*C] (keys above threshold, keys equal) per chunk
   uint2* chunk_before;     // [P*C] the same, summed over the tensor's earlier chunks
   uint32_t* chunk_sub;     // [P*C*(SW+1)] winners before each 1024-element sweep of a chunk,

@@ -30,7 +30,14 @@ struct WorkItem {
   uint32_t w, r, c, seg;
   ChunkDesc cd;
   size_t base;   // arena offset of the chunk
+  size_t slot;   // where the chunk's staged entries start in the staging arrays
+  uint32_t cap;  // how many entries the slot holds
 };
+
+// A chunk whose possible winners do not fit its staging slot is marked with this count and
+// staged not at all: the kernels that would read its staged entries read the chunk's elements
+// from the arenas instead (exact all the same; it takes massive ties or a large Top-K share).
+constexpr uint32_t kNotStaged = 0xFFFFFFFFu;
 
 __device__ __forceinline__ WorkItem work_item(const Tables& T, uint32_t i) {
   WorkItem it;
@@ -40,6 +47,11 @@ __device__ __forceinline__ WorkItem work_item(const Tables& T, uint32_t i) {
   it.cd = T.chunks[it.c];
   it.seg = it.r * T.L + it.cd.layer;
   it.base = (size_t)it.r * T.Npad + it.cd.off;
+  // a slot holds stage_num of every 16 elements of the chunk's range; slots of neighbouring
+  // chunks cannot overlap (floor(a/16) + floor(len/16) <= floor((a + len)/16)) and start on
+  // multiples of 4 entries (stage_num is 4, 8, 12 or 16), i.e. 16-byte aligned
+  it.slot = (size_t)it.r * T.stage_stride + (size_t)(it.cd.off >> 4) * T.stage_num;
+  it.cap = (it.cd.len >> 4) * T.stage_num;
   return it;
 }
 
@@ -150,7 +162,8 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
     for (uint32_t b = threadIdx.x; b < (uint32_t)kHistBins; b += kThreads) h[b] = 0;
     __syncthreads();
     uint32_t run = 0, runb = 0;   // staged so far: all entries, in-bin entries
-    bool direct = false;          // uniform: this chunk overflowed a buffer
+    bool direct = false;          // uniform: this chunk overflowed an LDS buffer
+    bool over = false;            // uniform: this chunk overflowed its staging slot, nothing more is staged
     for (int it = 0; it < SWEEPS; it += STEP) {   // uniform trip count: the scan needs every thread
       float xa[STEP][4];
       uint32_t key[STEP][4], take[STEP], inb[STEP], e[STEP];
@@ -199,13 +212,15 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
         all += (uint32_t)((total >> (16 * u)) & 0xFFFFu);
         allb += (uint32_t)((totalb >> (16 * u)) & 0xFFFFu);
       }
+      if (run + all > wi.cap) over = true;      // uniform (in-bin entries are among them: they fit if these do)
+      if (over) continue;                       // only the histogram above still matters for this chunk
       if (!direct && (run + all > kCap || runb + allb > kCapB)) {   // uniform: empty the buffers and go direct
         __syncthreads();
         for (uint32_t q = threadIdx.x; q < run; q += kThreads) {
-          T.stage_idx[wi.base + q] = li[q];
-          T.stage_val[wi.base + q] = lv[q];
+          T.stage_idx[wi.slot + q] = li[q];
+          T.stage_val[wi.slot + q] = lv[q];
         }
-        for (uint32_t q = threadIdx.x; q < runb; q += kThreads) T.stage_key[wi.base + q] = lb[q];
+        for (uint32_t q = threadIdx.x; q < runb; q += kThreads) T.stage_key[wi.slot + q] = lb[q];
         direct = true;
       }
 #pragma unroll
@@ -222,9 +237,9 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
               lv[pos] = xa[u][q];
               if (flag) lb[posb] = key[u][q];
             } else {
-              T.stage_idx[wi.base + pos] = jf;
-              T.stage_val[wi.base + pos] = xa[u][q];
-              if (flag) T.stage_key[wi.base + posb] = key[u][q];
+              T.stage_idx[wi.slot + pos] = jf;
+              T.stage_val[wi.slot + pos] = xa[u][q];
+              if (flag) T.stage_key[wi.slot + posb] = key[u][q];
             }
             ++pos;
             posb += flag;
@@ -236,26 +251,29 @@ __global__ __launch_bounds__(kThreads) void k_topk_stage(Tables T, StepArgs A) {
       run = before;
       runb = beforeb;
     }
-    if (threadIdx.x == 0) T.stage_n[wi.w] = make_uint2(run, runb);
+    if (threadIdx.x == 0) {
+      T.stage_n[wi.w] = over ? make_uint2(kNotStaged, 0u) : make_uint2(run, runb);
+      if (over) atomicAdd(&T.counts[3], 1u);     // running count, reported by evg_stats
+    }
     __syncthreads();
-    if (!direct) {
+    if (!direct && !over) {
       // the chunk's slot starts 16-byte aligned: whole quads stream out, the tail goes singly
       typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
       const uint32_t quads = run / 4, quadsb = runb / 4;
       for (uint32_t q = threadIdx.x; q < quads; q += kThreads) {
         __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(li + 4 * q),
-                                    reinterpret_cast<u32x4*>(T.stage_idx + wi.base) + q);
+                                    reinterpret_cast<u32x4*>(T.stage_idx + wi.slot) + q);
         __builtin_nontemporal_store(*reinterpret_cast<const f32x4*>(lv + 4 * q),
-                                    reinterpret_cast<f32x4*>(T.stage_val + wi.base) + q);
+                                    reinterpret_cast<f32x4*>(T.stage_val + wi.slot) + q);
       }
       for (uint32_t q = threadIdx.x; q < quadsb; q += kThreads)
         __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(lb + 4 * q),
-                                    reinterpret_cast<u32x4*>(T.stage_key + wi.base) + q);
+                                    reinterpret_cast<u32x4*>(T.stage_key + wi.slot) + q);
       for (uint32_t q = 4 * quads + threadIdx.x; q < run; q += kThreads) {
-        T.stage_idx[wi.base + q] = li[q];
-        T.stage_val[wi.base + q] = lv[q];
+        T.stage_idx[wi.slot + q] = li[q];
+        T.stage_val[wi.slot + q] = lv[q];
       }
-      for (uint32_t q = 4 * quadsb + threadIdx.x; q < runb; q += kThreads) T.stage_key[wi.base + q] = lb[q];
+      for (uint32_t q = 4 * quadsb + threadIdx.x; q < runb; q += kThreads) T.stage_key[wi.slot + q] = lb[q];
     }
 
     flush_hist<kHistBins>(h, T.hist + (size_t)wi.seg * kHistBins);
@@ -289,23 +307,36 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
   return v;
 }
 
+// Rank key and value of element q of a chunk, straight from the arenas (chunks that were not staged).
+__device__ __forceinline__ uint32_t arena_key(const Tables& T, const WorkItem& wi, uint32_t q, uint32_t by_value,
+                                              float* xv) {
+  const float x = T.x[wi.base + q];
+  const float h = by_value ? 0.0f : T.xhat[wi.base + q];
+  *xv = x;
+  return rank_key(x, h, by_value);
+}
+
 constexpr int kBatch = 8;    // 64-entry groups loaded together by a wavefront, to overlap their latency
 
 // Bits 8..0 of the in-bin keys that carry the 22-bit prefix found so far.  Matches are
 // rare (a 2^-22 slice of the key range), so they go straight to the tensor's histogram,
 // one atomic per distinct value per 64 entries.
-__global__ __launch_bounds__(kThreads) void k_topk_hist_low(Tables T) {
+__global__ __launch_bounds__(kThreads) void k_topk_hist_low(Tables T, StepArgs A) {
   const uint32_t n = T.counts[1];
   for (uint32_t i = wave_slot(); i < n; i += wave_slots()) {
     const WorkItem wi = work_item(T, i);
-    const uint32_t prefix = T.sel_prefix[wi.seg], ns = T.stage_n[wi.w].y;
+    const uint2 sn = T.stage_n[wi.w];
+    const bool staged = sn.x != kNotStaged;             // wave-uniform
+    const uint32_t prefix = T.sel_prefix[wi.seg], ns = staged ? sn.y : wi.cd.len;
     uint32_t* gh = T.hist + (size_t)wi.seg * kHistBins;
     for (uint32_t q0 = 0; q0 < ns; q0 += 64 * kBatch) {
       uint32_t key[kBatch];
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const uint32_t q = q0 + u * 64 + lane_id();
-        key[u] = q < ns ? T.stage_key[wi.base + q] : 0xFFFFFFFFu;   // no key has bit 31: never matches
+        key[u] = 0xFFFFFFFFu;                           // no key has bit 31: never matches
+        float unused;
+        if (q < ns) key[u] = staged ? T.stage_key[wi.slot + q] : arena_key(T, wi, q, A.topk_key, &unused);
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
@@ -327,14 +358,15 @@ __global__ __launch_bounds__(kThreads) void k_topk_hist_low(Tables T) {
 // Per chunk: how many staged keys exceed / equal the threshold key.  Every key above
 // the threshold is staged (its bin is >= the threshold's), so these are the chunk's counts;
 // entries staged without a key lie above the threshold's bin and exceed it.
-__global__ __launch_bounds__(kThreads) void k_topk_count(Tables T) {
+__global__ __launch_bounds__(kThreads) void k_topk_count(Tables T, StepArgs A) {
   const uint32_t n = T.counts[1];
   for (uint32_t i = wave_slot(); i < n; i += wave_slots()) {
     const WorkItem wi = work_item(T, i);
     const uint32_t t = T.sel_prefix[wi.seg];
     const uint2 sn = T.stage_n[wi.w];
-    const uint32_t ns = sn.y;
-    uint32_t g = sn.x - sn.y, e = 0;
+    const bool staged = sn.x != kNotStaged;             // wave-uniform
+    const uint32_t ns = staged ? sn.y : wi.cd.len;
+    uint32_t g = staged ? sn.x - sn.y : 0u, e = 0;
     for (uint32_t q0 = 0; q0 < ns; q0 += 64 * kBatch) {
       uint32_t key[kBatch];
       bool in[kBatch];
@@ -342,7 +374,9 @@ __global__ __launch_bounds__(kThreads) void k_topk_count(Tables T) {
       for (int u = 0; u < kBatch; ++u) {
         const uint32_t q = q0 + u * 64 + lane_id();
         in[u] = q < ns;
-        key[u] = in[u] ? T.stage_key[wi.base + q] : 0u;
+        key[u] = 0u;
+        float unused;
+        if (in[u]) key[u] = staged ? T.stage_key[wi.slot + q] : arena_key(T, wi, q, A.topk_key, &unused);
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
@@ -377,11 +411,13 @@ __global__ __launch_bounds__(64) void k_topk_chunkscan(Tables T) {
 // Stable compaction of a chunk's winners from its staged entries into the tensor's
 // message.  Also records where each 1024-element sweep of the chunk starts in the
 // message, so that the update pass can fetch exactly its part.
-__global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
+__global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T, StepArgs A) {
   const uint32_t n = T.counts[1];
   for (uint32_t i = wave_slot(); i < n; i += wave_slots()) {
     const WorkItem wi = work_item(T, i);
-    const uint32_t t = T.sel_prefix[wi.seg], ties = T.sel_krem[wi.seg], ns = T.stage_n[wi.w].x;
+    const uint32_t t = T.sel_prefix[wi.seg], ties = T.sel_krem[wi.seg];
+    const bool staged = T.stage_n[wi.w].x != kNotStaged;           // wave-uniform
+    const uint32_t ns = staged ? T.stage_n[wi.w].x : wi.cd.len;
     const uint2 before = T.chunk_before[wi.w];
     const size_t mbase = (size_t)wi.r * T.Ktot + T.layers[wi.cd.layer].msg_off;
     uint32_t* sub = T.chunk_sub + (size_t)wi.w * (T.SW + 1);
@@ -394,23 +430,36 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T) {
       uint32_t key[kBatch], j[kBatch];
       float val[kBatch];
       bool in[kBatch], flag[kBatch];
+      if (staged) {
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const uint32_t q = q0 + u * 64 + lane_id();
-        in[u] = q < ns;
-        j[u] = in[u] ? T.stage_idx[wi.base + q] : wi.cd.j0;
-        val[u] = in[u] ? T.stage_val[wi.base + q] : 0.0f;   // most staged entries win: fetch with the indices
-      }
-      // an entry with the in-bin flag finds its key in the chunk's key list, at its rank among
-      // the flagged entries; the others lie above the threshold's bin (any key above t will do)
+        for (int u = 0; u < kBatch; ++u) {
+          const uint32_t q = q0 + u * 64 + lane_id();
+          in[u] = q < ns;
+          j[u] = in[u] ? T.stage_idx[wi.slot + q] : wi.cd.j0;
+          val[u] = in[u] ? T.stage_val[wi.slot + q] : 0.0f;   // most staged entries win: fetch with the indices
+        }
+        // an entry with the in-bin flag finds its key in the chunk's key list, at its rank among
+        // the flagged entries; the others lie above the threshold's bin (any key above t will do)
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        flag[u] = (j[u] >> 31) != 0u;
-        j[u] &= 0x7FFFFFFFu;
-        const uint64_t mf = __ballot(flag[u]);
-        key[u] = 0xFFFFFFFFu;
-        if (flag[u]) key[u] = T.stage_key[wi.base + run_b + lanes_below(mf)];
-        run_b += __popcll(mf);
+        for (int u = 0; u < kBatch; ++u) {
+          flag[u] = (j[u] >> 31) != 0u;
+          j[u] &= 0x7FFFFFFFu;
+          const uint64_t mf = __ballot(flag[u]);
+          key[u] = 0xFFFFFFFFu;
+          if (flag[u]) key[u] = T.stage_key[wi.slot + run_b + lanes_below(mf)];
+          run_b += __popcll(mf);
+        }
+      } else {
+        // not staged: every element of the chunk, keys recomputed from the arenas
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          const uint32_t q = q0 + u * 64 + lane_id();
+          in[u] = q < ns;
+          j[u] = wi.cd.j0 + (in[u] ? q : 0u);
+          val[u] = 0.0f;
+          key[u] = 0u;
+          if (in[u]) key[u] = arena_key(T, wi, q, A.topk_key, &val[u]);
+        }
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {                // groups in index order
@@ -455,7 +504,7 @@ static void select_s(const Tables& t, const StepArgs& a, uint32_t grid, hipStrea
   k_topk_pick<0><<<segs, b, 0, s>>>(t);
   k_topk_stage<SWEEPS><<<g, b, 0, s>>>(t, a);
   k_topk_pick<1><<<segs, b, 0, s>>>(t);
-  k_topk_hist_low<<<g, b, 0, s>>>(t);
+  k_topk_hist_low<<<g, b, 0, s>>>(t, a);
   k_topk_pick<2><<<segs, b, 0, s>>>(t);
 }
 
@@ -471,11 +520,11 @@ hipError_t launch_topk_select(const Tables& t, const StepArgs& a, uint32_t chunk
   return hipGetLastError();
 }
 
-hipError_t launch_topk_send(const Tables& t, const StepArgs&, uint32_t, uint32_t grid, hipStream_t s) {
+hipError_t launch_topk_send(const Tables& t, const StepArgs& a, uint32_t, uint32_t grid, hipStream_t s) {
   const dim3 g(grid), b(kThreads);
-  k_topk_count<<<g, b, 0, s>>>(t);
+  k_topk_count<<<g, b, 0, s>>>(t, a);
   k_topk_chunkscan<<<dim3(t.S), dim3(64), 0, s>>>(t);
-  k_topk_pack<<<g, b, 0, s>>>(t);
+  k_topk_pack<<<g, b, 0, s>>>(t, a);
   return hipGetLastError();
 }
 

@@ -61,7 +61,7 @@ class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in
                 ("iters", "events_total", "events_full", "events_topk", "value_words", "index_words",
                  "bytes_sent", "regular_events", "regular_words", "near_tie_flags", "nonfinite_norms",
-                 "library_bytes")] + \
+                 "chunks_not_staged", "library_bytes")] + \
                [("events_full_rl", C.c_void_p), ("events_topk_rl", C.c_void_p), ("last_norm", C.c_void_p),
                 ("delta", C.c_void_p), ("last_event_iter", C.c_void_p), ("valid_l", C.c_void_p),
                 ("valid_r", C.c_void_p)]
@@ -264,7 +264,7 @@ class Ring:
                 keep[name] = np.zeros(S, dt)
                 setattr(st, name, keep[name].ctypes.data)
         _check(lib().evg_stats(self._h, C.byref(st)))
-        out = {n: int(getattr(st, n)) for n, _ in Stats._fields_[:12]}
+        out = {n: int(getattr(st, n)) for n, _ in Stats._fields_[:13]}
         for name, a in keep.items():
             out[name] = a.reshape(self.P, self.L)
         return out

@@ -49,7 +49,10 @@ def test_many_workers_small_tensors(evg, oracle_mod):
 def test_one_large_tensor_many_chunks(evg, oracle_mod, chunk):
     for ppm in (1, 1000, 333_333):
         w = inputs.Workload("big", 3, spec([300_001, 3]), 12, sigma0=0.05, decay=0.97, topk_ppm=ppm, seed=9)
-        run(evg, oracle_mod, w, 12, gpu=dict(chunk_elems=chunk))
+        ring, _ = run(evg, oracle_mod, w, 12, gpu=dict(chunk_elems=chunk))
+        # continuous keys: the large tensor's chunks all fit their staging slots (the 3-element
+        # tensor has no slot at all: a slot holds a share of every 16 elements)
+        assert ring.stats()["chunks_not_staged"] <= 3 * 12
 
 
 @pytest.mark.parametrize("chunk", [1024, 4096])
@@ -77,6 +80,9 @@ def test_ties_across_chunks(evg, oracle_mod, chunk):
 
     rep = lockstep(ring, orc, 16, grads=host, gpu_grads=dev, sample_messages=64)
     assert all(rep["bitwise"].values())
+    # with so many equal keys the possible winners of a chunk exceed its staging slot (a quarter of
+    # the chunk at this Top-K share): these chunks were selected straight from the arenas
+    assert ring.stats()["chunks_not_staged"] > 0
 
 
 def test_nonfinite_drift_is_counted_and_never_fires(evg, oracle_mod):

@@ -154,6 +154,9 @@ def test_full_size_full_length_run_matches_the_oracle_record(evg, say, i):
     assert np.array_equal(st["valid_l"], g["valid_l"]) and np.array_equal(st["valid_r"], g["valid_r"])
     np.testing.assert_allclose(st["delta"], g["delta"], rtol=4e-7, atol=1e-37)
     assert st["iters"] == iters and st["regular_events"] == P * L * iters
+    say(f"{tag} Top-K work granules selected from the arenas instead of their staging slots: {st['chunks_not_staged']} "
+        f"of {int(st['events_topk_rl'].astype(np.int64).sum())} Top-K events' granules; library-owned memory "
+        f"{st['library_bytes'] / 1e9:.2f} GB")
     say(f"{tag} {st['events_total']} events of {st['regular_events']} "
         f"({100.0 * st['events_total'] / st['regular_events']:.1f} % of the regular algorithm's messages), "
         f"{int(g['totals'][-1][3])} near ties: decisions, messages and parameters equal the oracle's")
