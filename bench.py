@@ -236,17 +236,18 @@ def main():
         upd_bytes = per_elem * elems
         achieved = upd_bytes / (avg_ms * 1e-3) / 1e9
         # What the dense-mailbox semantics cost at the granularity memory is written in: the dense
-        # 28 (or fewer) bytes per element, xhat := x for whole sends, each message read by its
-        # sender and both receivers (3 x 8 bytes per entry), and the write-back of every aligned
-        # 64-byte group of xhat and of the two mailboxes that holds a sent entry.  With K of n
-        # entries sent, spread evenly, a 16-float group holds one with probability 1 - (1 - K/n)^16.
+        # 28 (or fewer) bytes per element (a tensor that was sent whole has its xhat written instead
+        # of read: the same 4 bytes), each message read by its sender and both receivers (3 x 8 bytes
+        # per entry), and the write-back of every aligned 64-byte group of xhat and of the two
+        # mailboxes that holds a sent entry.  With K of n entries sent, spread evenly, a 16-float
+        # group holds one with probability 1 - (1 - K/n)^16.
         dense = per_elem - UPDATE_TOPK_BYTES_PER_FIRED_ELEM_PER_RHO * rho * f_topk
         ev_topk = st["events_topk_rl"].astype(np.float64).sum(axis=0)        # per tensor, all workers and steps
         K = np.array([max(1, min(int(n), -(-int(n) * w.topk_ppm // 1_000_000))) if w.topk_ppm else 0
                       for n in w.layer_numel], np.float64)
         share = K / numel
         dirty = 1.0 - (1.0 - share) ** 16
-        floor = dense * elems + 4 * f_full * elems + float((ev_topk * numel * (12 * dirty + 24 * share)).sum()) / args.steps
+        floor = dense * elems + float((ev_topk * numel * (12 * dirty + 24 * share)).sum()) / args.steps
         counters = measured_counters(w.name) if not (args.diag_grad_buffer or args.trigger_kind or args.delivery_delay
                                                      or args.xhat_reset or args.plain_sgd or args.seed is not None) else None
         upd_counters = (counters or {}).get("kernels", {}).get("k_update", {})

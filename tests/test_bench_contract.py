@@ -65,6 +65,6 @@ def test_json_line_of_a_short_run(monkeypatch, capsys):
     assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["unit"] == "GB/s"
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12 and r["launches"] == 5
     assert abs(r["achieved"] - r["algorithmic_bytes_per_launch"] / (r["avg_launch_ms"] * 1e-3) / 1e9) <= 1e-6 * r["achieved"]
-    # whole-tensor sends: the line-granular floor is the dense bytes plus xhat := x of the fired tensors
+    # whole-tensor sends: nothing is patched, the line-granular floor is the algorithmic figure
     assert r["line_granular_floor_bytes_per_launch"] >= r["algorithmic_bytes_per_launch"]
     assert r["traffic"] is None and r["traffic_measured_at"] is None      # no counter run is recorded for configuration 2
