@@ -813,7 +813,7 @@ std::vector<Piece> state_pieces(evg_ctx* c) {
       {t.valid_l, S}, {t.valid_r, S}, {t.fired, S}, {t.near_tie, S},
       {t.ev_full, S * 4}, {t.ev_topk, S * 4}, {t.near_cnt, S * 4}, {t.nonfinite_cnt, S * 4},
       {t.slope_hist, S * t.hist_len * 4}, {t.slope_cnt, S * 4}, {t.partials, sweeps * 8},
-      {t.it, sizeof(IterState)}};
+      {t.it, sizeof(IterState)}, {t.counts, 4 * sizeof(uint32_t)}};   // counts[3] is a running counter
   if (t.partials_hat) { v.push_back({t.partials_hat, sweeps * 8}); v.push_back({t.xhat_sq, S * 8}); }
   if (t.hist) v.push_back({t.hist, S * kHistBins * 4});
   return v;
@@ -822,7 +822,7 @@ std::vector<Piece> state_pieces(evg_ctx* c) {
 StateHeader state_header(evg_ctx* c) {
   StateHeader h{};
   std::memcpy(h.magic, "EVGSTATE", 8);
-  h.version = 2;
+  h.version = 3;
   h.P = c->t.P; h.L = c->t.L; h.C = c->t.C; h.SW = c->t.SW; h.S = c->t.S;
   h.hist_len = c->t.hist_len;
   h.topk_ppm = c->cfg.topk_ppm;

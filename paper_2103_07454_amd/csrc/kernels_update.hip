@@ -16,6 +16,20 @@
 // float4 is written back only if its 64-byte group changed.
 #include "evg_device.h"
 
+// Build-time variants of the Top-K message handling, kept so that the measurements behind the
+// defaults can be repeated (EVG_EXTRA_FLAGS="-DEVG_PATCH_WINDOWS=2" python -m paper_2103_07454_amd.build):
+//   EVG_PATCH_WINDOWS  LDS windows the three messages of a workgroup are scattered into: 3 = one each
+//                      (default: one barrier pair), 2 = two used in turn, 1 = one after the other
+//                      (less LDS, more barriers; measured 1-2 % slower);
+//   EVG_UPDATE_SPW     sweeps per workgroup when messages are applied: 2 (default) or 1 (5-7 % slower).
+// Results are identical in every variant.
+#ifndef EVG_PATCH_WINDOWS
+#define EVG_PATCH_WINDOWS 3
+#endif
+#ifndef EVG_UPDATE_SPW
+#define EVG_UPDATE_SPW 2
+#endif
+
 namespace evg {
 
 __device__ __forceinline__ float4 ld4(const float* p) { return ld4s(p); }
@@ -140,11 +154,14 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   __shared__ double ws[4 * SPW];
   // LDS: the windows of the three patches; once those are consumed the same
   // storage holds the key histogram
-  __shared__ __attribute__((aligned(16))) float pv[TOPK ? 3 * SPW * kSweep : 4];
+  constexpr int NWIN = EVG_PATCH_WINDOWS;
+  constexpr int kWinFloats = NWIN * SPW * kSweep > (HISTA ? kHistBins : 0) ? NWIN * SPW * kSweep : kHistBins;
+  __shared__ __attribute__((aligned(16))) float pv[TOPK ? kWinFloats : 4];
   __shared__ uint32_t pm[3 * 32 * SPW];
   constexpr uint32_t kWin = SPW * kSweep, kWinWords = 32 * SPW;
   uint32_t* hA = reinterpret_cast<uint32_t*>(pv);
-  static_assert(!HISTA || (TOPK && 3 * kSweep >= kHistBins), "histogram must fit the patch windows");
+  static_assert(!HISTA || TOPK, "the histogram shares the patch windows' storage");
+  static_assert(NWIN >= 1 && NWIN <= 3, "EVG_PATCH_WINDOWS is 1, 2 or 3");
   const uint32_t groups = T.SW / SPW;      // workgroups per chunk (SW is a multiple of SPW)
   const uint32_t c = blockIdx.x / groups, sub0 = (blockIdx.x % groups) * SPW, r = blockIdx.y;
   const ChunkDesc cd = T.chunks[c];
@@ -205,18 +222,52 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
       if (s0.n | s1.n | s2.n) {          // uniform
         for (uint32_t q = threadIdx.x; q < 3 * kWinWords; q += kThreads) pm[q] = 0;
         __syncthreads();
-        scatter_slice<SPW>(T, s0, j_lo, pv, pm);
-        scatter_slice<SPW>(T, s1, j_lo, pv + kWin, pm + kWinWords);
-        scatter_slice<SPW>(T, s2, j_lo, pv + 2 * kWin, pm + 2 * kWinWords);
-        __syncthreads();
+        // applies window w (values) / mask m to array a of every sweep and writes changed groups back
+        auto apply = [&](const float* w, const uint32_t* m, float (*a)[4], float* arena) {
 #pragma unroll
-        for (int u = 0; u < SPW; ++u) {
-          const uint32_t b0 = take_patch(pv, pm, u, ha[u]);
-          const uint32_t b1 = take_patch(pv + kWin, pm + kWinWords, u, la[u]);
-          const uint32_t b2 = take_patch(pv + 2 * kWin, pm + 2 * kWinWords, u, ra[u]);
-          if (live[u] && b0) st4t<STREAM>(T.xhat + base + e[u], make_float4(ha[u][0], ha[u][1], ha[u][2], ha[u][3]));
-          if (live[u] && b1) st4t<STREAM>(T.mbox_l + base + e[u], make_float4(la[u][0], la[u][1], la[u][2], la[u][3]));
-          if (live[u] && b2) st4t<STREAM>(T.mbox_r + base + e[u], make_float4(ra[u][0], ra[u][1], ra[u][2], ra[u][3]));
+          for (int u = 0; u < SPW; ++u) {
+            const uint32_t b = take_patch(w, m, u, a[u]);
+            if (live[u] && b) st4t<STREAM>(arena + base + e[u], make_float4(a[u][0], a[u][1], a[u][2], a[u][3]));
+          }
+        };
+        if (NWIN == 3) {
+          scatter_slice<SPW>(T, s0, j_lo, pv, pm);
+          scatter_slice<SPW>(T, s1, j_lo, pv + kWin, pm + kWinWords);
+          scatter_slice<SPW>(T, s2, j_lo, pv + 2 * kWin, pm + 2 * kWinWords);
+          __syncthreads();
+          apply(pv, pm, ha, T.xhat);
+          apply(pv + kWin, pm + kWinWords, la, T.mbox_l);
+          apply(pv + 2 * kWin, pm + 2 * kWinWords, ra, T.mbox_r);
+        } else if (NWIN == 2) {
+          // two windows in turn: while one is read the next message is scattered into the other
+          scatter_slice<SPW>(T, s0, j_lo, pv, pm);
+          __syncthreads();
+          scatter_slice<SPW>(T, s1, j_lo, pv + kWin, pm + kWinWords);
+          apply(pv, pm, ha, T.xhat);
+          __syncthreads();
+          scatter_slice<SPW>(T, s2, j_lo, pv, pm + 2 * kWinWords);
+          apply(pv + kWin, pm + kWinWords, la, T.mbox_l);
+          __syncthreads();
+          apply(pv, pm + 2 * kWinWords, ra, T.mbox_r);
+        } else {
+          // one window, the three messages one after the other (empty ones skipped: uniform)
+          if (s0.n) {
+            scatter_slice<SPW>(T, s0, j_lo, pv, pm);
+            __syncthreads();
+            apply(pv, pm, ha, T.xhat);
+            __syncthreads();
+          }
+          if (s1.n) {
+            scatter_slice<SPW>(T, s1, j_lo, pv, pm + kWinWords);
+            __syncthreads();
+            apply(pv, pm + kWinWords, la, T.mbox_l);
+            __syncthreads();
+          }
+          if (s2.n) {
+            scatter_slice<SPW>(T, s2, j_lo, pv, pm + 2 * kWinWords);
+            __syncthreads();
+            apply(pv, pm + 2 * kWinWords, ra, T.mbox_r);
+          }
         }
       }
     }
@@ -348,7 +399,7 @@ static void launch_update_v(const Tables& t, const StepArgs& a, uint32_t dist, u
   // two sweeps per workgroup where the pass carries the Top-K extras and a chunk has them
   // (measured: four are slower again, LDS and registers then hold occupancy down)
   if (TOPK && HISTA && t.SW % 2 == 0)
-    launch_update_w<NORM, TOPK, HISTA, (TOPK && HISTA) ? 2 : 1>(t, a, dist, grad_mode, s);
+    launch_update_w<NORM, TOPK, HISTA, (TOPK && HISTA) ? EVG_UPDATE_SPW : 1>(t, a, dist, grad_mode, s);
   else
     launch_update_w<NORM, TOPK, HISTA, 1>(t, a, dist, grad_mode, s);
 }
