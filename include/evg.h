@@ -118,7 +118,12 @@ typedef struct {
                                    EVG_ACCESS_STREAM: non-temporal (rings far larger than the
                                    caches); EVG_ACCESS_CACHED: ordinary accesses (rings that fit
                                    the 256 MB last-level cache); EVG_ACCESS_AUTO: cached if the
-                                   five arenas together take at most 128 MB                    */
+                                   five arenas together take at most 128 MB.  A cached ring that
+                                   sends whole tensors without delivery delay also skips the copy
+                                   kernel: each receiver fetches what its neighbours send inside
+                                   the update pass, from a copy of x the library keeps (two more
+                                   arrays of the ring's size, library-owned); an iteration is then
+                                   two kernel launches instead of four                           */
   evg_synth synth;
   /* DEVICE arenas owned by the caller, each P * evg_padded_numel() floats,
    * 16-byte aligned, non-overlapping, alive until evg_destroy.  Worker r's

@@ -266,7 +266,7 @@ static uint32_t stage_num_for(uint32_t topk_ppm) {
 }
 
 static uint64_t table_bytes(uint64_t P, uint64_t L, uint64_t C, uint64_t SW, uint64_t hist_len, uint64_t Npad,
-                            uint64_t ktot, uint64_t stage_num, bool topk, bool norm_diff) {
+                            uint64_t ktot, uint64_t stage_num, bool topk, bool norm_diff, bool pull) {
   const uint64_t S = P * L, PC = P * C;
   uint64_t total = 0;
   auto add = [&total](uint64_t count, uint64_t elem) {
@@ -281,6 +281,7 @@ static uint64_t table_bytes(uint64_t P, uint64_t L, uint64_t C, uint64_t SW, uin
   add(S * hist_len, 4); add(S, 4); add(S, 4); add(S, 4); // slope_hist, slope_cnt, seg_woff_full/topk
   add(4, 4); add(1, sizeof(IterState)); add(kDecayTable, 8);
   add(PC, 4);                                            // work_full
+  if (pull) add(2 * P * Npad, 4);                        // xsnap
   if (topk) {
     add(PC, 4); add(S * kHistBins, 4); add(S, 4); add(S, 4); add(PC, 8);
     const uint64_t stage = P * (Npad / 16 * stage_num);
@@ -362,6 +363,9 @@ static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_st
   c->cfg.layer_fan_in = nullptr;
   c->stream = static_cast<hipStream_t>(hip_stream);
   c->chunk_elems = ce;
+  // 256 MB of last-level cache on MI355X; a ring whose arenas take at most half of it is
+  // served from there and does better with ordinary than with streaming accesses
+  c->cached = cfg->access_mode == EVG_ACCESS_CACHED || (cfg->access_mode == EVG_ACCESS_AUTO && small_ring);
   const uint32_t P = cfg->P, L = cfg->L;
   std::vector<LayerDesc> layers(L);
   std::vector<ChunkDesc> chunks;
@@ -439,7 +443,8 @@ static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_st
   HIP_OR_FREE(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   if (use_scratch) {
     const uint64_t need = table_bytes(P, L, C, t.SW, t.hist_len, Npad, ktot, t.stage_num, cfg->topk_ppm != 0,
-                                      cfg->trigger_kind == EVG_TRIGGER_NORM_DIFF);
+                                      cfg->trigger_kind == EVG_TRIGGER_NORM_DIFF,
+                                      c->cached && !cfg->topk_ppm && !cfg->delivery_delay);
     if (need > kScratchBytes) {
       evg_destroy(c);
       return fail(EVG_ERR_INVALID, "this configuration needs %llu bytes of tables; the static scratch block "
@@ -469,9 +474,6 @@ static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_st
     c->arena_base = g_scratch_base[dev];
     c->arena_dev = dev;
   }
-  // 256 MB of last-level cache on MI355X; a ring whose arenas take at most half of it is
-  // served from there and does better with ordinary than with streaming accesses
-  c->cached = cfg->access_mode == EVG_ACCESS_CACHED || (cfg->access_mode == EVG_ACCESS_AUTO && small_ring);
   const uint64_t full_grid = (uint64_t)P * C;
   c->work_grid = (uint32_t)(full_grid < (uint64_t)cus * 8 ? full_grid : (uint64_t)cus * 8);
   TRY_OR_FREE(c->dalloc(&d_chunks, C, false));
@@ -514,6 +516,10 @@ static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_st
     t.decay_len = kDecayTable;
   }
   TRY_OR_FREE(c->dalloc(&t.work_full, P * C, true));
+  // cache-resident ring, whole tensors, same-iteration delivery: the update pass fetches the sends
+  // itself from a copy of x it keeps (one more array of the ring's size, library-owned)
+  const bool pull = c->cached && !cfg->topk_ppm && !cfg->delivery_delay;
+  if (pull) TRY_OR_FREE(c->dalloc(&t.xsnap, 2 * (uint64_t)P * Npad, false));
   if (cfg->topk_ppm) {
     TRY_OR_FREE(c->dalloc(&t.work_topk, P * C, true));
     TRY_OR_FREE(c->dalloc(&t.hist, S * kHistBins, true));
@@ -539,6 +545,10 @@ static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_st
   HIP_OR_FREE(hipMemcpyAsync(t.delta, dinit.data(), S * sizeof(float), hipMemcpyHostToDevice, c->stream));
   HIP_OR_FREE(hipMemsetAsync(t.last_event, 0xFF, S * sizeof(int32_t), c->stream));
   HIP_OR_FREE(hipMemcpyAsync(t.xhat, t.x, arena_bytes, hipMemcpyDeviceToDevice, c->stream));
+  if (t.xsnap) {     // step 1 reads copy 0; both are set so that either parity finds x
+    HIP_OR_FREE(hipMemcpyAsync(t.xsnap, t.x, arena_bytes, hipMemcpyDeviceToDevice, c->stream));
+    HIP_OR_FREE(hipMemcpyAsync(t.xsnap + (uint64_t)P * Npad, t.x, arena_bytes, hipMemcpyDeviceToDevice, c->stream));
+  }
   HIP_OR_FREE(hipMemsetAsync(t.vel, 0, arena_bytes, c->stream));
   HIP_OR_FREE(launch_norm(t, cfg->trigger_kind == EVG_TRIGGER_NORM_DIFF, c->stream));
   HIP_OR_FREE(hipStreamSynchronize(c->stream));   // host staging buffers above go out of scope
@@ -589,10 +599,11 @@ static evg_status enqueue_step(evg_ctx* c, const StepArgs& a, bool timed) {
     Phase ph(c, EVG_PH_TRIGGER);
     HIP_TRY(launch_trigger(t, a, c->stream));
     HIP_TRY(launch_scan(t, a, c->stream));
-    HIP_TRY(launch_expand(t, c->stream));
+    HIP_TRY(launch_expand(t, a, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
   }
-  if (!a.delay) {      // with delayed delivery the mailboxes are written after the update
+  if (!a.delay && !a.pull) {      // with delayed delivery the mailboxes are written after the update;
+                                  // a cache-resident ring's receivers fetch the sends in the update pass
     Phase ph(c, EVG_PH_SEND_FULL);
     HIP_TRY(launch_copy(t, a, c->chunk_elems, c->work_grid, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
@@ -645,6 +656,7 @@ static evg_status fixed_args(evg_ctx* c, const float* grad, StepArgs* out) {
   a.delay = g.delivery_delay;
   a.hist_fused = (g.topk_ppm && g.norm_mode == EVG_NORM_FUSED) ? 1u : 0u;
   a.cached = c->cached ? 1u : 0u;
+  a.pull = c->t.xsnap ? 1u : 0u;
   a.xhat_reset = (g.xhat_reset && g.topk_ppm) ? 1u : 0u;
   const bool norm_diff = g.trigger_kind == EVG_TRIGGER_NORM_DIFF;
   // fused + whole-tensor sends: xhat's norm is a scalar per tensor and xhat is never read
@@ -881,6 +893,12 @@ evg_status evg_state_import(evg_ctx* c, const void* blob, uint64_t size) {
   for (const Piece& p : state_pieces(c)) {
     HIP_TRY(hipMemcpy(p.dev, in, p.bytes, hipMemcpyHostToDevice));
     in += p.bytes;
+  }
+  // the library's copy of x follows the caller's arena, which holds the saved parameters again
+  if (c->t.xsnap) {
+    const size_t arena = (size_t)c->t.P * c->t.Npad;
+    HIP_TRY(hipMemcpy(c->t.xsnap, c->t.x, arena * 4, hipMemcpyDeviceToDevice));
+    HIP_TRY(hipMemcpy(c->t.xsnap + arena, c->t.x, arena * 4, hipMemcpyDeviceToDevice));
   }
   c->iters = got.iters;
   c->last_iter = got.last_iter;

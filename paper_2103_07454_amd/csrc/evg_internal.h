@@ -47,6 +47,9 @@ struct Tables {
   const ChunkDesc* chunks;
   const LayerDesc* layers;
   float* x; float* xhat; float* mbox_l; float* mbox_r; float* vel;
+  float* xsnap;            // [2][P*Npad] or null: copies of x that the update pass of one iteration leaves
+                           // for the next one, two in turn (cache-resident rings with whole-tensor
+                           // sends: the receivers then fetch what a neighbour sends, no copy kernel)
   double* partials;        // [P*C*SW] per 1024-element sweep of a chunk: sum of squared drift, or
                            // of squared x when the trigger compares norms
   double* partials_hat;    // [P*C*SW] sum of squared xhat (norm-difference trigger only)
@@ -106,6 +109,7 @@ struct StepArgs {
   uint32_t from_device;    // take k and decay^k from IterState instead of the two fields here
   uint32_t xhat_reset;     // a Top-K event resets the whole tensor's xhat to x
   uint32_t cached;         // the arenas fit the last-level cache: ordinary instead of streaming accesses
+  uint32_t pull;           // whole-tensor sends are fetched by the receivers inside the update pass
   uint32_t key0, key1;
   double decay_pow;        // decay^k
   float spike_prob, spike_gain;
@@ -120,7 +124,7 @@ hipError_t launch_update(const Tables& t, const StepArgs& a, uint32_t dist, uint
 hipError_t launch_trigger(const Tables& t, const StepArgs& a, hipStream_t s);
 hipError_t launch_begin(const Tables& t, hipStream_t s);
 hipError_t launch_scan(const Tables& t, const StepArgs& a, hipStream_t s);
-hipError_t launch_expand(const Tables& t, hipStream_t s);
+hipError_t launch_expand(const Tables& t, const StepArgs& a, hipStream_t s);
 hipError_t launch_copy(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid, hipStream_t s);
 hipError_t launch_deliver(const Tables& t, uint32_t chunk_elems, uint32_t grid, hipStream_t s);
 hipError_t launch_topk_select(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid,

@@ -83,10 +83,18 @@ __device__ __forceinline__ void trigger_segment(const Tables& T, const StepArgs&
   if (A.topk_on) { T.idx_hash[seg] = 0ull; T.msg_hash[seg] = 0ull; }   // k_topk_pack adds to them
 }
 
+// The step's bookkeeping (normally the scan kernel's first thread does it).
+__device__ __forceinline__ void close_step(const Tables& T, const StepArgs& A) {
+  T.it->k_next = step_k(T, A) + 1;
+  T.it->iters += 1;
+}
+
 __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {
   const uint32_t seg = blockIdx.x * (kThreads / 64) + wave_id();
   if (seg >= T.S) return;           // whole wavefront leaves; no workgroup barrier below
   trigger_segment(T, A, seg);
+  // receivers fetch the sends themselves: no chunk lists, so no scan kernel follows
+  if (A.pull && seg == 0 && lane_id() == 0) close_step(T, A);
 }
 
 // First kernel of a replayable step: one thread moves the device's iteration on.
@@ -131,8 +139,7 @@ __device__ __forceinline__ void scan_segments(const Tables& T, const StepArgs& A
   }
   if (threadIdx.x == 0) {
     T.counts[0] = tf; T.counts[1] = tt; T.counts[2] = ts;
-    T.it->k_next = step_k(T, A) + 1;
-    T.it->iters += 1;
+    close_step(T, A);
   }
 }
 
@@ -147,6 +154,10 @@ __global__ __launch_bounds__(1024) void k_scan(Tables T, StepArgs A) {
 __global__ __launch_bounds__(1024) void k_front(Tables T, StepArgs A) {
   __shared__ uint32_t ws[16];
   for (uint32_t seg = wave_id(); seg < T.S; seg += 16) trigger_segment(T, A, seg);
+  if (A.pull) {                     // uniform: no lists are needed
+    if (threadIdx.x == 0) close_step(T, A);
+    return;
+  }
   __syncthreads();                  // the flags written above are read below by other wavefronts
   scan_segments<true>(T, A, ws);
 }
@@ -208,14 +219,14 @@ hipError_t launch_begin(const Tables& t, hipStream_t s) {
 }
 
 hipError_t launch_scan(const Tables& t, const StepArgs& a, hipStream_t s) {
-  if (one_front(t)) return hipSuccess;
+  if (one_front(t) || a.pull) return hipSuccess;
   if (scan_expands(t)) k_scan<true><<<dim3(1), dim3(1024), 0, s>>>(t, a);
   else k_scan<false><<<dim3(1), dim3(1024), 0, s>>>(t, a);
   return hipGetLastError();
 }
 
-hipError_t launch_expand(const Tables& t, hipStream_t s) {
-  if (scan_expands(t)) return hipSuccess;
+hipError_t launch_expand(const Tables& t, const StepArgs& a, hipStream_t s) {
+  if (scan_expands(t) || a.pull) return hipSuccess;
   const uint32_t grid = (t.S + 3) / 4;
   k_expand<<<dim3(grid), dim3(kThreads), 0, s>>>(t);
   return hipGetLastError();

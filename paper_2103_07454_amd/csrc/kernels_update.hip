@@ -149,7 +149,13 @@ __device__ __forceinline__ void block_sums(const double v[SPW], double* ws, doub
 // streams best; two halve the per-workgroup costs of the Top-K work (message look-up,
 // barriers, clearing and merging the histogram).
 // STREAM: non-temporal accesses to the arenas (rings larger than the last-level cache).
-template <int DIST, bool GRADBUF, int NORM, bool TOPK, bool HISTA, int SPW, bool STREAM>
+// PULL: whole-tensor sends of this iteration have NOT been copied into the mailboxes: where a
+// neighbour sent, its values are fetched from the copy of x that the previous update pass left
+// (x itself is being overwritten by its owner in this very launch), used, and written into the
+// mailbox here; and the new x is also written to the other of the two copies for the next
+// iteration (two copies in turn: the one read now is written by nobody in this launch).  Fewer
+// launches per iteration for rings that live in the cache, where launches are what costs.
+template <int DIST, bool GRADBUF, int NORM, bool TOPK, bool HISTA, int SPW, bool STREAM, bool PULL = false>
 __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   __shared__ double ws[4 * SPW];
   // LDS: the windows of the three patches; once those are consumed the same
@@ -167,6 +173,15 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   const ChunkDesc cd = T.chunks[c];
   const uint32_t seg = r * T.L + cd.layer;
   const bool vl = T.valid_l[seg] != 0, vr = T.valid_r[seg] != 0;
+  // PULL: did my neighbours send this tensor whole in this iteration? (then vl / vr are set)
+  const uint32_t lw = (r + T.P - 1) % T.P, rw = (r + 1) % T.P;
+  const bool from_l = PULL && T.fired[lw * T.L + cd.layer] == 1;
+  const bool from_r = PULL && T.fired[rw * T.L + cd.layer] == 1;
+  // the trigger kernel has counted this step already: step n reads copy (n-1) & 1, writes copy n & 1
+  const size_t arena = (size_t)T.P * T.Npad;
+  const uint64_t step_no = PULL ? T.it->iters : 0;
+  const float* snap_in = PULL ? T.xsnap + ((step_no + 1) & 1) * arena : nullptr;
+  float* snap_out = PULL ? T.xsnap + (step_no & 1) * arena : nullptr;
   // xhat := x for the whole tensor: after a whole send, or after any event when a Top-K
   // event is read as resetting the tensor's xhat
   const uint32_t my_event = T.fired[seg];
@@ -196,8 +211,16 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
         if (!A.plain_sgd) v4 = ld4t<STREAM>(T.vel + base + e[u]);   // uniform
         xa[u][0] = x4.x; xa[u][1] = x4.y; xa[u][2] = x4.z; xa[u][3] = x4.w;
         va[u][0] = v4.x; va[u][1] = v4.y; va[u][2] = v4.z; va[u][3] = v4.w;
-        if (vl) { const float4 t = ld4t<STREAM>(T.mbox_l + base + e[u]); la[u][0] = t.x; la[u][1] = t.y; la[u][2] = t.z; la[u][3] = t.w; }
-        if (vr) { const float4 t = ld4t<STREAM>(T.mbox_r + base + e[u]); ra[u][0] = t.x; ra[u][1] = t.y; ra[u][2] = t.z; ra[u][3] = t.w; }
+        if (from_l) {        // the put of my left neighbour, carried out by its receiver
+          const float4 t = ld4t<STREAM>(snap_in + (size_t)lw * T.Npad + cd.off + e[u]);
+          la[u][0] = t.x; la[u][1] = t.y; la[u][2] = t.z; la[u][3] = t.w;
+          st4t<STREAM>(T.mbox_l + base + e[u], t);
+        } else if (vl) { const float4 t = ld4t<STREAM>(T.mbox_l + base + e[u]); la[u][0] = t.x; la[u][1] = t.y; la[u][2] = t.z; la[u][3] = t.w; }
+        if (from_r) {
+          const float4 t = ld4t<STREAM>(snap_in + (size_t)rw * T.Npad + cd.off + e[u]);
+          ra[u][0] = t.x; ra[u][1] = t.y; ra[u][2] = t.z; ra[u][3] = t.w;
+          st4t<STREAM>(T.mbox_r + base + e[u], t);
+        } else if (vr) { const float4 t = ld4t<STREAM>(T.mbox_r + base + e[u]); ra[u][0] = t.x; ra[u][1] = t.y; ra[u][2] = t.z; ra[u][3] = t.w; }
         if (sent_whole) {
           // the whole tensor was sent in this iteration: xhat becomes the x just read
           ha[u][0] = xa[u][0]; ha[u][1] = xa[u][1]; ha[u][2] = xa[u][2]; ha[u][3] = xa[u][3];
@@ -320,6 +343,7 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
           }
         }
         st4t<STREAM>(T.x + base + e[u], make_float4(xa[u][0], xa[u][1], xa[u][2], xa[u][3]));
+        if (PULL) st4t<STREAM>(snap_out + base + e[u], make_float4(xa[u][0], xa[u][1], xa[u][2], xa[u][3]));
         if (!A.plain_sgd) st4t<STREAM>(T.vel + base + e[u], make_float4(va[u][0], va[u][1], va[u][2], va[u][3]));
         if (NORM == 1) drift_acc(acc[u], xa[u], ha[u], nv);
         if (NORM >= 2) square_acc(acc[u], xa[u], nv);
@@ -382,6 +406,13 @@ template <int NORM, bool TOPK, bool HISTA, int SPW>
 static void launch_update_w(const Tables& t, const StepArgs& a, uint32_t dist, uint32_t grad_mode,
                             hipStream_t s) {
   const dim3 grid(t.C * (t.SW / SPW), t.P), block(kThreads);
+  if (!TOPK && a.pull) {     // the host sets pull only for cache-resident rings with whole-tensor sends
+    constexpr bool NT = false, NH = false;
+    if (grad_mode == 1) k_update<0, true, NORM, NT, NH, 1, false, true><<<grid, block, 0, s>>>(t, a);
+    else if (dist == 0) k_update<0, false, NORM, NT, NH, 1, false, true><<<grid, block, 0, s>>>(t, a);
+    else k_update<1, false, NORM, NT, NH, 1, false, true><<<grid, block, 0, s>>>(t, a);
+    return;
+  }
   if (a.cached) {
     if (grad_mode == 1) k_update<0, true, NORM, TOPK, HISTA, SPW, false><<<grid, block, 0, s>>>(t, a);
     else if (dist == 0) k_update<0, false, NORM, TOPK, HISTA, SPW, false><<<grid, block, 0, s>>>(t, a);
