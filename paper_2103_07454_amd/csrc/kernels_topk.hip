@@ -139,7 +139,9 @@ __global__ __launch_bounds__(kThreads) void k_topk_pick(Tables T) {
 // fields of one 64-bit word (a sweep stages at most 1024 entries).  The entries are
 // compacted in LDS and written out once per chunk.
 //
-// What is staged per chunk, both lists in ascending index order at the chunk's arena offset:
+// What is staged per chunk, both lists in ascending index order in the chunk's staging slot
+// (a share of the chunk's length; a chunk with more possible winners than that is marked and
+// left to the arena paths of the kernels below):
 //   (index | in-bin flag in bit 31, value)  for every element whose bin is >= b: all possible winners;
 //   key                                     for those of them whose bin IS b (flag set): only they
 //                                           still have to be compared with the exact threshold,
