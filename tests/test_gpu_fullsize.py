@@ -113,3 +113,57 @@ def test_full_size_config5_properties_over_many_iterations(evg, say):
     assert st["events_full"] == P * L and st["events_total"] == st["events_full"] + st["events_topk"]
     assert st["bytes_sent"] == 8 * (st["value_words"] + st["index_words"])
     assert torch.isfinite(ring.x).all()
+
+
+@pytest.mark.timeout(600)
+def test_one_very_large_tensor_properties(evg, say):
+    """A single tensor of 2^27 + 5 elements (16 385 work granules, a Top-K message of 13.4 million
+    entries) next to a 3-element one, three workers: far beyond what the CPU oracle can step, so the
+    Top-K messages are recomputed on the GPU with a stable sort and the bookkeeping is checked through
+    properties that hold at any size."""
+    import torch
+    n_big = (1 << 27) + 5
+    tensors = [inputs.TensorSpec("big", (n_big,), 64, "weight"), inputs.TensorSpec("tiny", (3,), 64, "bias")]
+    w = inputs.Workload("huge_tensor", 3, tensors, 4, sigma0=0.05, decay=0.97, topk_ppm=100_000, seed=31)
+    P, L = w.P, w.L
+    rng = np.random.Generator(np.random.Philox(key=77))
+    x0 = np.broadcast_to((rng.standard_normal(w.N, dtype=np.float32) * np.float32(0.1))[None, :], (P, w.N))
+    ring = evg.Ring.from_workload(w, x0)
+    del x0
+    off = ring.layout.offsets.astype(np.int64)
+    K = (n_big * w.topk_ppm + 999_999) // 1_000_000
+    sl = slice(int(off[0]), int(off[0]) + n_big)
+    for k in range(4):
+        before = [(ring.x[r, sl].clone(), ring.xhat[r, sl].clone()) for r in range(P)] if k >= 1 else None
+        ring.step(k)
+        d = ring.decisions()
+        fired = d["fired"]
+        if k == 0:
+            assert (fired == 1).all()
+        else:
+            assert (d["norm"][fired > 0] >= d["delta_before"][fired > 0]).all()
+            assert (d["norm"][fired == 0] < d["delta_before"][fired == 0]).all()
+        if k >= 1:
+            ih, mh = ring.message_hashes()
+            for r in range(P):
+                xs, hs = before[r]
+                if fired[r, 0] == 2:
+                    key = (xs - hs).abs().view(torch.int32)
+                    want = torch.sort(torch.sort(key, descending=True, stable=True).indices[:K]).values
+                    idx, val = ring.message(r, 0)
+                    assert idx.size == K and np.array_equal(idx.astype(np.int64), want.cpu().numpy()), (k, r)
+                    assert np.array_equal(val, xs[want].cpu().numpy())
+                    new_hat = hs.clone()
+                    new_hat[want] = xs[want]
+                    assert torch.equal(ring.xhat[r, sl], new_hat)
+                    assert torch.equal(ring.mbox_l[(r + 1) % P, sl], new_hat) and torch.equal(ring.mbox_r[(r - 1) % P, sl], new_hat)
+                    assert ih[r, 0] != 0 and mh[r, 0] != 0
+                    del key, want, new_hat
+                elif fired[r, 0] == 0:
+                    assert torch.equal(ring.xhat[r, sl], hs) and ih[r, 0] == 0
+            say(f"[one very large tensor] iteration {k}: decisions {fired[:, 0].tolist()}, messages of {K} entries equal a stable sort's")
+        del before
+    st = ring.stats()
+    assert st["events_full"] == P * L and st["value_words"] - st["index_words"] == P * w.N
+    assert st["chunks_not_staged"] <= st["events_topk"]            # at most the 3-element tensor's granules
+    assert torch.isfinite(ring.x).all()
