@@ -264,7 +264,9 @@ evg_status evg_message(evg_ctx* c, uint32_t r, uint32_t l, uint32_t* idx, float*
  * generator (z += 0x9E3779B97F4A7C15; z = (z ^ z >> 30) * 0xBF58476D1CE4E5B9;
  * z = (z ^ z >> 27) * 0x94D049BB133111EB; z ^ z >> 31).  0 where (r, l) sent no Top-K
  * message.  They let a caller compare every message of a step with another implementation
- * without copying the messages themselves to the host.  Waits for the stream. */
+ * without copying the messages themselves to the host.  Computed by this call from the message
+ * buffers (one small kernel on the context's stream; nothing is added to evg_step); waits for
+ * the stream. */
 evg_status evg_message_hashes(evg_ctx* c, uint64_t* idx_hash, uint64_t* msg_hash);
 
 /* Final model: out[j] = mean over workers of x[r][j] (last line of Algorithm B).

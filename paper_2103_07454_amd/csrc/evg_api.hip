@@ -781,8 +781,9 @@ evg_status evg_message(evg_ctx* c, uint32_t r, uint32_t l, uint32_t* idx, float*
 evg_status evg_message_hashes(evg_ctx* c, uint64_t* idx_hash, uint64_t* msg_hash) {
   if (!c) return fail(EVG_ERR_INVALID, "context is NULL");
   const Tables& t = c->t;
-  HIP_TRY(hipStreamSynchronize(c->stream));
   const bool live = c->cfg.topk_ppm && c->messages_live;
+  if (live) HIP_TRY(launch_message_hashes(t, c->stream));    // from the message buffers of the last step
+  HIP_TRY(hipStreamSynchronize(c->stream));
   if (idx_hash) {
     if (live) HIP_TRY(hipMemcpy(idx_hash, t.idx_hash, (size_t)t.S * 8, hipMemcpyDeviceToHost));
     else std::memset(idx_hash, 0, (size_t)t.S * 8);

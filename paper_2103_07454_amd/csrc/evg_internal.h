@@ -80,8 +80,8 @@ struct Tables {
   uint32_t* chunk_sub;     // [P*C*(SW+1)] winners before each 1024-element sweep of a chunk,
                            // as message slots (entry 0 = the chunk's first slot)
   uint32_t* msg_idx; float* msg_val;          // [P*Ktot]
-  unsigned long long* idx_hash;               // [S] fingerprints of this step's Top-K messages:
-  unsigned long long* msg_hash;               // sums of mixed indices / mixed (value, index) pairs
+  unsigned long long* idx_hash;               // [S] fingerprints of the last step's Top-K messages (sums of
+  unsigned long long* msg_hash;               // mixed indices / mixed (value, index) pairs), filled on request
   IterState* it;
   const double* decay_tab;   // decay^k for k < decay_len (replayable steps only)
   uint32_t decay_len;
@@ -132,5 +132,6 @@ hipError_t launch_topk_select(const Tables& t, const StepArgs& a, uint32_t chunk
 hipError_t launch_topk_send(const Tables& t, const StepArgs& a, uint32_t chunk_elems, uint32_t grid,
                             hipStream_t s);
 hipError_t launch_average(const Tables& t, float* out, hipStream_t s);
+hipError_t launch_message_hashes(const Tables& t, hipStream_t s);
 
 }  // namespace evg

@@ -427,7 +427,6 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T, StepArgs A) {
     uint32_t run_g = before.x, run_e = before.y;
     uint32_t run_b = 0;                                 // in-bin entries of this chunk met so far
     uint32_t per_sweep[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // winners per sweep (wave-uniform)
-    unsigned long long hi = 0ull, hm = 0ull;            // this lane's share of the fingerprints
     for (uint32_t q0 = 0; q0 < ns; q0 += 64 * kBatch) {
       uint32_t key[kBatch], j[kBatch];
       float val[kBatch];
@@ -473,23 +472,21 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T, StepArgs A) {
           const uint32_t pos = g + (eq < ties ? eq : ties);
           T.msg_idx[mbase + pos] = j[u];
           T.msg_val[mbase + pos] = val[u];
-          hi += mix64((unsigned long long)j[u]);
-          hm += mix64(((unsigned long long)__float_as_uint(val[u]) << 32) | (unsigned long long)j[u]);
         }
+        // entries ascend, so a group of 64 touches only the sweeps between its first and its last
+        // entry's (all three values below are wave-uniform)
         const uint32_t sw = (j[u] - wi.cd.j0) / (uint32_t)kSweep;
+        const uint64_t mi = __ballot(in[u]);
+        const uint32_t last = mi ? 63u - (uint32_t)__builtin_clzll(mi) : 0u;
+        const uint32_t sw_lo = __shfl(sw, 0, 64), sw_hi = __shfl(sw, last, 64);
 #pragma unroll
         for (uint32_t s2 = 0; s2 < 8; ++s2)
-          if (s2 < T.SW) per_sweep[s2] += __popcll(__ballot(win && sw == s2));
+          if (s2 >= sw_lo && s2 <= sw_hi) per_sweep[s2] += __popcll(__ballot(win && sw == s2));
         run_g += __popcll(mg);
         run_e += __popcll(me);
       }
     }
-    // integer sums: the order in which chunks add their shares does not change the result
-    hi = wave_sum_u64(hi);
-    hm = wave_sum_u64(hm);
     if (lane_id() == 0) {
-      atomicAdd(&T.idx_hash[wi.seg], hi);
-      atomicAdd(&T.msg_hash[wi.seg], hm);
       uint32_t at = first;
 #pragma unroll
       for (uint32_t s2 = 0; s2 < 8; ++s2)
@@ -497,6 +494,39 @@ __global__ __launch_bounds__(kThreads) void k_topk_pack(Tables T, StepArgs A) {
       sub[T.SW] = at;
     }
   }
+}
+
+// Fingerprints of the messages of the last step, computed when asked for (evg_message_hashes):
+// one workgroup per (worker, tensor) walks the packed message.  Integer sums: the order of
+// summation does not change the result.
+__global__ __launch_bounds__(kThreads) void k_message_hashes(Tables T) {
+  __shared__ unsigned long long ws[2 * (kThreads / 64)];
+  const uint32_t seg = blockIdx.x;
+  unsigned long long hi = 0ull, hm = 0ull;
+  if (T.fired[seg] == 2) {          // uniform for the workgroup
+    const LayerDesc ld = T.layers[seg % T.L];
+    const size_t mbase = (size_t)(seg / T.L) * T.Ktot + ld.msg_off;
+    for (uint32_t q = threadIdx.x; q < ld.K; q += kThreads) {
+      const unsigned long long j = T.msg_idx[mbase + q];
+      hi += mix64(j);
+      hm += mix64(((unsigned long long)__float_as_uint(T.msg_val[mbase + q]) << 32) | j);
+    }
+  }
+  hi = wave_sum_u64(hi);
+  hm = wave_sum_u64(hm);
+  if (lane_id() == 0) { ws[wave_id()] = hi; ws[kThreads / 64 + wave_id()] = hm; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long a = 0ull, b = 0ull;
+    for (int w = 0; w < kThreads / 64; ++w) { a += ws[w]; b += ws[kThreads / 64 + w]; }
+    T.idx_hash[seg] = a;
+    T.msg_hash[seg] = b;
+  }
+}
+
+hipError_t launch_message_hashes(const Tables& t, hipStream_t s) {
+  k_message_hashes<<<dim3(t.S), dim3(kThreads), 0, s>>>(t);
+  return hipGetLastError();
 }
 
 template <int SWEEPS>

@@ -80,7 +80,6 @@ __device__ __forceinline__ void trigger_segment(const Tables& T, const StepArgs&
     }
   }
   T.fired[seg] = code;
-  if (A.topk_on) { T.idx_hash[seg] = 0ull; T.msg_hash[seg] = 0ull; }   // k_topk_pack adds to them
 }
 
 // The step's bookkeeping (normally the scan kernel's first thread does it).
