@@ -151,6 +151,41 @@ def test_genuine_ties_fire_and_are_flagged(evg, oracle_mod):
     assert np.array_equal(ring.state("x"), orc.state("x"))
 
 
+@pytest.mark.parametrize("delta,steps,want_near,want_fire", [
+    # threshold 1: 8 and 9 float spacings above, 16 and 18 half-spacings below, the tie, and far values
+    (1.0, [8 * 2.0 ** -23, 9 * 2.0 ** -23, -16 * 2.0 ** -24, -18 * 2.0 ** -24, 0.0, 1.0, -0.5],
+     [True, False, True, False, True, False, False], [True, True, False, False, True, True, False]),
+    # threshold 2^-126: 1e-6 * delta is exactly 8 denormal units, the band's edge itself is outside
+    (2.0 ** -126, [7 * 2.0 ** -149, 8 * 2.0 ** -149, 9 * 2.0 ** -149, -7 * 2.0 ** -149, -8 * 2.0 ** -149, 0.0],
+     [True, False, False, True, False, True], [True, True, True, False, False, True]),
+])
+def test_near_tie_band_edges_on_the_gpu(evg, oracle_mod, delta, steps, want_near, want_fire):
+    """The 1e-6 band is the only licence for a decision to differ between the two sides, so the HIP
+    path must draw it exactly where the oracle does (float arithmetic, denormals kept, strict <).
+    One single-element tensor per case; iteration 0 moves x from 0 to delta + step exactly (plain SGD
+    with lr 1 and a gradient buffer, nothing fires at drift 0), iteration 1 tests it."""
+    import torch
+    P, L = 3, len(steps)
+    norms = (np.float32(delta) + np.array(steps, np.float64)).astype(np.float32)
+    assert all(float(n) == delta + s for n, s in zip(norms, steps))          # exactly representable
+    x0 = np.zeros((P, L), np.float32)
+    kw = dict(lr=1.0, momentum=0.0, grad_mode=1, thr_mode=0, thr_fixed=float(delta), force_first=0)
+    ring = evg.Ring(x0, [1] * L, None, **kw)
+    orc = oracle_mod.Oracle(x0, np.array([1] * L, np.uint64), None, **kw)
+    g = np.broadcast_to(-norms, (P, L)).astype(np.float32)
+    gd = torch.from_numpy(ring.layout.pad(g)).cuda()
+    zero = torch.zeros_like(gd)
+    for k, (gh, gdev) in enumerate(((g, gd), (np.zeros_like(g), zero))):
+        ring.step(k, gdev)
+        orc.step(k, grad=gh)
+        a, b = ring.decisions(), orc.decisions()
+        for key in ("fired", "near_tie", "norm", "delta_before"):
+            assert np.array_equal(a[key], b[key]), (k, key)
+    assert np.array_equal(a["norm"][0], norms)
+    assert (a["near_tie"][0] != 0).tolist() == want_near and (a["fired"][0] != 0).tolist() == want_fire
+    assert ring.stats()["near_tie_flags"] == orc.totals()["near_tie_flags"] == P * sum(want_near)
+
+
 @pytest.mark.parametrize("seed", [7, 20260303])
 @pytest.mark.parametrize("i", [2, 5])
 def test_other_seeds(evg, oracle_mod, i, seed):
