@@ -176,7 +176,8 @@ typedef struct {
 enum {
   EVG_PH_NORM = 0,       /* separate drift-norm pass (EVG_NORM_SEPARATE only)        */
   EVG_PH_TRIGGER = 1,    /* norm finalisation, trigger test, thresholds, work lists  */
-  EVG_PH_SEND_FULL = 2,  /* whole-tensor copies into xhat and both mailboxes         */
+  EVG_PH_SEND_FULL = 2,  /* whole-tensor copies into both mailboxes (no samples where
+                            the receivers fetch the sends inside the update pass)     */
   EVG_PH_TOPK_SELECT = 3,/* threshold-key search for the Top-K set                   */
   EVG_PH_TOPK_SEND = 4,  /* pack (index, value) messages, put them                   */
   EVG_PH_UPDATE = 5,     /* fused averaging + momentum SGD (+ next drift norms)      */
