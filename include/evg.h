@@ -54,9 +54,9 @@ enum { EVG_ACCESS_AUTO = 0, EVG_ACCESS_STREAM = 1, EVG_ACCESS_CACHED = 2 };
  * Algorithm B): element j of tensor l of worker r at iteration k is
  * sigma_l(k) * z, z drawn from a Philox4x32-10 stream with key = seed and
  * counter (block, l, k, r).  Normals: block j/4 gives elements 4(j/4) .. +3 by Box-Muller on
- * its word pairs (0,1) and (2,3).  Student-t(3): blocks 3(j/4), +1, +2 give twelve words, element
- * 4(j/4)+i takes words 3i, 3i+1, 3i+2 as t = z0 sqrt(3 / (z1^2 - 2 ln u)), (z0, z1) the
- * Box-Muller pair of the first two and u the uniform of the third.
+ * its word pairs (0,1) and (2,3).  Student-t(3): blocks 2(j/4), +1 give eight words, element
+ * 4(j/4)+i takes words 2i, 2i+1 as t = sqrt(3 (u^(-2/3) - 1)) cos(2 pi v), u and v their uniforms
+ * (the polar method: radius and angle of a spherical bivariate t).
  * sigma_l(k) = sigma0 [/ sqrt(fan_in_l)] * decay^k; with
  * probability spike_prob a whole (worker, iteration) gradient is multiplied by
  * spike_gain. */

@@ -79,6 +79,8 @@ def lib():
         l.orc_uniform01.argtypes = [C.c_uint32]
         l.orc_log.restype = C.c_float
         l.orc_log.argtypes = [C.c_float]
+        l.orc_exp.restype = C.c_float
+        l.orc_exp.argtypes = [C.c_float]
         l.orc_sincos2pi.argtypes = [C.c_float, f32p, f32p]
         l.orc_normal4.argtypes = [u32p, f32p]
         l.orc_topk_count.restype = C.c_uint64
@@ -236,6 +238,10 @@ def uniform01(w):
 
 def log_poly(u):
     return float(lib().orc_log(float(u)))
+
+
+def exp_poly(y):
+    return float(lib().orc_exp(float(y)))
 
 
 def sincos2pi(u):

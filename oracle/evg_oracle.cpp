@@ -45,8 +45,7 @@
 //       copies still change only at the sent indices.
 //   R8  gradients are synthetic: a counter-based Philox4x32-10 stream turned
 //       into normals by Box-Muller with fixed polynomial log/sin/cos; Student-t(3)
-//       variates take three uniforms each (one Box-Muller pair and the squared radius
-//       of a second one), four variates per three Philox blocks.
+//       variates by the polar method, two uniforms each, four variates per two blocks.
 //
 // parity unpinned: R6's choice of key and of which xhat entries reset cannot be
 // checked against the authors' code (not available); everything else is pinned
@@ -167,6 +166,22 @@ void sincos2pi_poly(float u, float* c_out, float* s_out) {
   }
 }
 
+// exp(y) for 0 <= y < 80 from +, * and fma only: y = n ln2 + r with n = floor(y / ln2 + 1/2)
+// and |r| <= 0.35 (ln2 split in two parts so that r is accurate), the Taylor series of exp(r)
+// to the sixth power, and an exact scaling by 2^n through the exponent field.
+float exp_poly(float y) {
+  const int n = (int)(y * 1.44269502f + 0.5f);
+  float r = std::fmaf(-(float)n, 0.693145752f, y);
+  r = std::fmaf(-(float)n, 1.42860677e-6f, r);
+  float p = std::fmaf(r, 1.38888892e-3f, 8.33333377e-3f);
+  p = std::fmaf(r, p, 4.16666679e-2f);
+  p = std::fmaf(r, p, 0.166666672f);
+  p = std::fmaf(r, p, 0.5f);
+  p = std::fmaf(r, p, 1.0f);
+  p = std::fmaf(r, p, 1.0f);
+  return u2f(f2u(p) + ((uint32_t)n << 23));
+}
+
 // Four normals from one Philox block: Box-Muller on (w0,w1) and on (w2,w3).
 void normal4(const uint32_t w[4], float z[4]) {
   for (int h = 0; h < 2; ++h) {
@@ -236,27 +251,25 @@ struct Oracle {
         for (uint64_t i = 0; i < 4 && j0 + i < n; ++i) g[j0 + i] = sg * z[i];
       }
     } else {
-      // Student-t with 3 degrees of freedom, t = z0 / sqrt(chi2_3 / 3) with chi2_3 = z1^2 + E:
-      // (z0, z1) is one Box-Muller pair and E = -2 ln u is the squared radius of a second,
-      // independent pair (a chi-square with 2 degrees of freedom), so three uniforms make one
-      // variate.  Elements 4g .. 4g+3 share the three Philox blocks 3g, 3g+1, 3g+2 of the
-      // (tensor, iteration, worker) stream: element 4g+i takes words 3i, 3i+1, 3i+2 of the twelve.
+      // Student-t with 3 degrees of freedom by the polar method (Bailey, Math. Comp. 62, 1994): the
+      // components of a spherical bivariate t have squared radius R^2 with
+      // P(R^2 > s) = (1 + s/nu)^(-nu/2), so R^2 = nu (u^(-2/nu) - 1) for a uniform u, and
+      // t = R cos(2 pi v) for a second uniform v is Student-t(nu).  Two uniforms make one variate:
+      // elements 4g .. 4g+3 share the Philox blocks 2g, 2g+1 of the (tensor, iteration, worker)
+      // stream, element 4g+i takes words 2i (radius) and 2i+1 (angle) of the eight.
       for (uint64_t j0 = 0; j0 < n; j0 += 4) {
-        uint32_t w[12];
-        for (uint32_t b = 0; b < 3; ++b) {
-          const uint32_t ctr[4] = {(uint32_t)(3 * (j0 >> 2) + b), l, (uint32_t)k, r};
+        uint32_t w[8];
+        for (uint32_t b = 0; b < 2; ++b) {
+          const uint32_t ctr[4] = {(uint32_t)(2 * (j0 >> 2) + b), l, (uint32_t)k, r};
           philox4x32_10(ctr, key, w + 4 * b);
         }
         for (uint64_t i = 0; i < 4 && j0 + i < n; ++i) {
-          const float ua = uniform01(w[3 * i]), ub = uniform01(w[3 * i + 1]), uc = uniform01(w[3 * i + 2]);
-          const float rad = std::sqrt(-2.0f * log_poly(ua));
+          const float u = uniform01(w[2 * i]), v = uniform01(w[2 * i + 1]);
+          const float y = 0.666666687f * -log_poly(u);          // -(2/3) ln u >= 0
+          const float rad = std::sqrt(3.0f * (exp_poly(y) - 1.0f));
           float c, s;
-          sincos2pi_poly(ub, &c, &s);
-          const float z0 = rad * c, z1 = rad * s;
-          const float e2 = -2.0f * log_poly(uc);
-          const float q = std::fmaf(z1, z1, e2);
-          const float t = z0 * std::sqrt(3.0f / q);
-          g[j0 + i] = sg * t;
+          sincos2pi_poly(v, &c, &s);
+          g[j0 + i] = sg * (rad * c);
         }
       }
     }
@@ -295,6 +308,7 @@ void orc_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) 
 }
 float orc_uniform01(uint32_t w) { return uniform01(w); }
 float orc_log(float u) { return log_poly(u); }
+float orc_exp(float y) { return exp_poly(y); }
 void orc_sincos2pi(float u, float* c, float* s) { sincos2pi_poly(u, c, s); }
 void orc_normal4(const uint32_t* w, float* z) { normal4(w, z); }
 

@@ -208,17 +208,31 @@ __device__ __forceinline__ void normals4(const Rand4& r, float z[4]) {
   }
 }
 
-// Student-t with 3 degrees of freedom from three random words: t = z0 / sqrt((z1^2 + E) / 3),
-// where (z0, z1) is the Box-Muller pair of words (a, b) and E = -2 ln u(c) is a chi-square with
-// two degrees of freedom (the squared radius of a second, independent pair).
-__device__ __forceinline__ float student_t3(uint32_t wa, uint32_t wb, uint32_t wc) {
-  const float rad = __builtin_sqrtf(-2.0f * ln_series(unit_open(wa)));
+// e^y for 0 <= y < 80 with only + * fma: the nearest multiple n of ln 2 is taken out in two
+// parts (high and low word of ln 2), the remainder's exponential is its Taylor polynomial of
+// degree six, and 2^n is added into the exponent field.
+__device__ __forceinline__ float exp_series(float y) {
+  const int n = (int)(y * 1.44269502f + 0.5f);
+  const float nf = (float)n;
+  const float r = __builtin_fmaf(-nf, 1.42860677e-6f, __builtin_fmaf(-nf, 0.693145752f, y));
+  float p = __builtin_fmaf(r, 1.38888892e-3f, 8.33333377e-3f);
+  p = __builtin_fmaf(r, p, 4.16666679e-2f);
+  p = __builtin_fmaf(r, p, 0.166666672f);
+  p = __builtin_fmaf(r, p, 0.5f);
+  p = __builtin_fmaf(r, p, 1.0f);
+  p = __builtin_fmaf(r, p, 1.0f);
+  return __uint_as_float(__float_as_uint(p) + ((uint32_t)n << 23));
+}
+
+// Student-t with 3 degrees of freedom from two random words by the polar method (Bailey 1994):
+// a spherical bivariate t has squared radius 3 (u^(-2/3) - 1) for a uniform u, and its first
+// component, radius times the cosine of a uniform angle, is Student-t(3).
+__device__ __forceinline__ float student_t3(uint32_t wr, uint32_t wa) {
+  const float y = 0.666666687f * -ln_series(unit_open(wr));
+  const float rad = __builtin_sqrtf(3.0f * (exp_series(y) - 1.0f));
   float c, s;
-  turn_cos_sin(unit_open(wb), c, s);
-  const float z0 = rad * c, z1 = rad * s;
-  const float e2 = -2.0f * ln_series(unit_open(wc));
-  const float q = __builtin_fmaf(z1, z1, e2);
-  return z0 * __builtin_sqrtf(3.0f / q);
+  turn_cos_sin(unit_open(wa), c, s);
+  return rad * c;
 }
 
 // Key that ranks elements for Top-K: the bit pattern of a non-negative float is

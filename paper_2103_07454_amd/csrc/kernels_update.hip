@@ -138,7 +138,7 @@ __device__ __forceinline__ void block_sums(const double v[SPW], double* ws, doub
   __syncthreads();
 }
 
-// DIST: 0 normal (one Philox block per float4), 1 Student-t(3) (three blocks per float4).
+// DIST: 0 normal (one Philox block per float4), 1 Student-t(3) (two blocks per float4).
 // GRADBUF: gradients come from a caller buffer.
 // NORM: what the pass accumulates for the next trigger test: 0 nothing, 1 the sweep's squared
 // drift, 2 its squared x (xhat is then not read at all), 3 its squared x and squared xhat.
@@ -310,16 +310,15 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) g[u][i] = sg * z[i];
           } else {
-            // four variates from the three Philox blocks 3g, 3g+1, 3g+2 of this float4 (g = index / 4):
-            // variate i takes words 3i, 3i+1, 3i+2 of the twelve
-            const uint32_t b0 = 3u * ((cd.j0 + e[u]) >> 2);
+            // four variates from the two Philox blocks 2g, 2g+1 of this float4 (g = index / 4):
+            // variate i takes words 2i (radius) and 2i+1 (angle) of the eight
+            const uint32_t b0 = ((cd.j0 + e[u]) >> 2) << 1;
             const Rand4 ra = philox(b0, cd.layer, k_iter, r, A.key0, A.key1);
             const Rand4 rb = philox(b0 + 1u, cd.layer, k_iter, r, A.key0, A.key1);
-            const Rand4 rc = philox(b0 + 2u, cd.layer, k_iter, r, A.key0, A.key1);
-            g[u][0] = sg * student_t3(ra.w[0], ra.w[1], ra.w[2]);
-            g[u][1] = sg * student_t3(ra.w[3], rb.w[0], rb.w[1]);
-            g[u][2] = sg * student_t3(rb.w[2], rb.w[3], rc.w[0]);
-            g[u][3] = sg * student_t3(rc.w[1], rc.w[2], rc.w[3]);
+            g[u][0] = sg * student_t3(ra.w[0], ra.w[1]);
+            g[u][1] = sg * student_t3(ra.w[2], ra.w[3]);
+            g[u][2] = sg * student_t3(rb.w[0], rb.w[1]);
+            g[u][3] = sg * student_t3(rb.w[2], rb.w[3]);
           }
           if (A.spike_prob > 0.0f) {
             const Rand4 sp = philox(0u, 0xFFFFFFFFu, k_iter, r, A.key0, A.key1);

@@ -68,6 +68,17 @@ def test_log_polynomial_against_libm(oracle_mod):
         assert abs(oracle_mod.log_poly(u) - ref) <= 3e-7 * abs(ref) + 2e-8
 
 
+def test_exp_polynomial_against_libm(oracle_mod):
+    rng = np.random.default_rng(6)
+    ys = np.concatenate([rng.random(20000).astype(np.float32) * np.float32(11.2),
+                         np.float32(2.0) ** -rng.integers(1, 30, 2000).astype(np.float32),
+                         np.array([0.0, 0.34657359, 0.346574, 0.6931472, 11.09, 1e-8], np.float32)])
+    for y in ys:
+        ref = math.exp(float(y))
+        assert abs(oracle_mod.exp_poly(y) - ref) <= 4e-7 * ref
+    assert oracle_mod.exp_poly(0.0) == 1.0
+
+
 def test_sincos_polynomial_against_libm(oracle_mod):
     us = np.concatenate([np.random.default_rng(4).random(20000).astype(np.float32),
                          np.arange(0, 1, 1 / 64, dtype=np.float32),
@@ -115,21 +126,17 @@ def test_counter_layout(oracle_mod):
         for j in range(g.size):
             z = oracle_mod.normal4(philox_bigint([j // 4, l, k, r], key))
             assert g[j] == z[j % 4]
-    # Student-t(3): elements 4g .. 4g+3 share Philox blocks 3g, 3g+1, 3g+2; element 4g+i takes words
-    # 3i (radius of its normal pair), 3i+1 (angle), 3i+2 (the chi-square(2) part of the denominator)
+    # Student-t(3), polar method: elements 4g .. 4g+3 share Philox blocks 2g, 2g+1; element 4g+i takes
+    # word 2i for the radius, R^2 = 3 (u^(-2/3) - 1), and word 2i+1 for the angle
     ot = _orc(oracle_mod, tensors, P=4, seed=seed, sigma0=1.0, dist=1)
     for (r, k, l) in [(2, 9, 0), (0, 0, 1), (3, 4, 2)]:
         g = ot.grad_tensor(r, k, l)
         for j in range(g.size):
-            words = []
-            for b in range(3):
-                words += philox_bigint([3 * (j // 4) + b, l, k, r], key)
+            words = philox_bigint([2 * (j // 4), l, k, r], key) + philox_bigint([2 * (j // 4) + 1, l, k, r], key)
             i = j % 4
-            ua, ub, uc = (((w >> 9) + 0.5) / 2**23 for w in words[3 * i:3 * i + 3])
-            rad = math.sqrt(-2 * math.log(ua))
-            z0, z1 = rad * math.cos(2 * math.pi * ub), rad * math.sin(2 * math.pi * ub)
-            want = z0 * math.sqrt(3 / (z1 * z1 - 2 * math.log(uc)))
-            assert abs(g[j] - want) < 1e-5 * max(1, abs(want)), (r, k, l, j)
+            u, v = (((w >> 9) + 0.5) / 2**23 for w in words[2 * i:2 * i + 2])
+            want = math.sqrt(3 * (u ** (-2 / 3) - 1)) * math.cos(2 * math.pi * v)
+            assert abs(g[j] - want) < 2e-5 * max(1, abs(want)) + 2e-4, (r, k, l, j)
 
 
 def test_normal_distribution(oracle_mod):

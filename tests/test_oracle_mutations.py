@@ -58,10 +58,12 @@ MUTANTS = [
     ("decay_off_by_one", "std::pow(cfg.decay, (double)k)", "std::pow(cfg.decay, (double)k + 1)"),
     ("spike_counter_moved", "{0u, 0xFFFFFFFFu, (uint32_t)k, r}", "{0u, 0xFFFFFFFEu, (uint32_t)k, r}"),
     ("spike_draw_from_other_word", "return uniform01(w[0]) < cfg.spike_prob;", "return uniform01(w[1]) < cfg.spike_prob;"),
-    ("student_t_degrees", "std::sqrt(3.0f / q)", "std::sqrt(2.0f / q)"),
-    ("student_t_denominator_reuses_the_angle_word", "uc = uniform01(w[3 * i + 2]);", "uc = uniform01(w[3 * i + 1]);"),
-    ("student_t_blocks_overlap", "(uint32_t)(3 * (j0 >> 2) + b)", "(uint32_t)((j0 >> 2) + b)"),
-    ("student_t_chi_square_without_the_normal_term", "std::fmaf(z1, z1, e2)", "e2"),
+    ("student_t_degrees", "std::sqrt(3.0f * (exp_poly(y) - 1.0f))", "std::sqrt(2.0f * (exp_poly(y) - 1.0f))"),
+    ("student_t_exponent", "0.666666687f * -log_poly(u)", "0.5f * -log_poly(u)"),
+    ("student_t_angle_reuses_the_radius_word", "v = uniform01(w[2 * i + 1]);", "v = uniform01(w[2 * i]);"),
+    ("student_t_blocks_overlap", "(uint32_t)(2 * (j0 >> 2) + b)", "(uint32_t)((j0 >> 2) + b)"),
+    ("student_t_radius_without_minus_one", "(exp_poly(y) - 1.0f)", "exp_poly(y)"),
+    ("exp_series_term", "p = std::fmaf(r, p, 0.166666672f);", "p = std::fmaf(r, p, 0.125f);"),
     # delayed delivery and the other reading of a Top-K event
     ("delayed_messages_land_at_once", "const bool now = c.delivery_delay == 0;", "const bool now = true;"),
     ("xhat_reset_ignored", "if (c.xhat_reset)\n", "if (false)\n"),
