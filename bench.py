@@ -270,8 +270,10 @@ def main():
             # Student-t gradients: the generator, not memory, bounds the pass
             ops = valu * elems / (avg_ms * 1e-3) / 1e12
             out["roofline"] = {"kernel": "k_update", "bound": "alu", "achieved": ops, "peak": ALU_PEAK_TLANEOPS,
-                               "unit": "T lane-instructions/s", "frac": ops / ALU_PEAK_TLANEOPS, "traffic": None,
+                               "unit": "T lane-instructions/s", "frac": ops / ALU_PEAK_TLANEOPS, "traffic": traffic,
                                "avg_launch_ms": avg_ms, "launches": n_upd,
+                               "algorithmic_bytes_per_launch": upd_bytes,
+                               "line_granular_floor_bytes_per_launch": floor,
                                "valu_instructions_per_element": valu,
                                "valu_measured_at": {"file": counters["file"]},
                                "hbm_achieved_GBps": achieved, "hbm_frac": achieved / HBM_PEAK_GBS}
