@@ -104,6 +104,9 @@ def main():
                     help="iterations recorded into the one graph (must divide --steps)")
     ap.add_argument("--xhat-reset", type=int, default=0,
                     help="1 = a Top-K event resets the whole tensor's xhat (not a benchmark configuration)")
+    ap.add_argument("--topk-ppm", type=int, default=None,
+                    help="another Top-K share, in parts per million (not a benchmark configuration: shows how "
+                         "the update pass's distance to its algorithmic bytes depends on the share sent)")
     ap.add_argument("--diag-grad-buffer", action="store_true",
                     help="diagnostic only (not the named workload): gradients from a fixed device buffer")
     args = ap.parse_args()
@@ -119,6 +122,8 @@ def main():
     w = inputs.config(args.config) if args.seed is None else inputs.config(args.config, args.seed)
     if args.plain_sgd:
         w = w.scaled(momentum=0.0)
+    if args.topk_ppm is not None:
+        w = w.scaled(topk_ppm=args.topk_ppm)
     x0 = w.x0()[None, :]                       # common start; uploaded once per worker slice
     x0 = np.broadcast_to(x0, (w.P, w.N))
 
@@ -210,7 +215,8 @@ def main():
         "config": {"workload": w.name + ("+DIAG_GRAD_BUFFER" if args.diag_grad_buffer else "")
                    + ("+NORM_DIFF_TRIGGER" if args.trigger_kind else "")
                    + ("+DELAYED_DELIVERY" if args.delivery_delay else "")
-                   + ("+XHAT_RESET" if args.xhat_reset else "") + ("+PLAIN_SGD" if args.plain_sgd else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N, "seed": w.seed,
+                   + ("+XHAT_RESET" if args.xhat_reset else "") + ("+PLAIN_SGD" if args.plain_sgd else "")
+                   + (f"+TOPK_PPM_{args.topk_ppm}" if args.topk_ppm is not None else ""), "P": w.P, "tensors": w.L, "elements_per_worker": w.N, "seed": w.seed,
                    "threshold": "adaptive" if w.thr_mode else "fixed", "topk_ppm": w.topk_ppm,
                    "chunk_elems": args.chunk or (2048 if 5 * 4 * w.P * evg.padded_numel(w.layer_numel) <= (128 << 20)
                                                  else 8192),
@@ -249,7 +255,8 @@ def main():
         dirty = 1.0 - (1.0 - share) ** 16
         floor = dense * elems + float((ev_topk * numel * (12 * dirty + 24 * share)).sum()) / args.steps
         counters = measured_counters(w.name) if not (args.diag_grad_buffer or args.trigger_kind or args.delivery_delay
-                                                     or args.xhat_reset or args.plain_sgd or args.seed is not None) else None
+                                                     or args.xhat_reset or args.plain_sgd or args.seed is not None
+                                                     or args.topk_ppm is not None) else None
         upd_counters = (counters or {}).get("kernels", {}).get("k_update", {})
         traffic = upd_counters.get("traffic_bytes")
         out["roofline"] = {"kernel": "k_update", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
