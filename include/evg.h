@@ -122,8 +122,12 @@ typedef struct {
                                    sends whole tensors without delivery delay also skips the copy
                                    kernel: each receiver fetches what its neighbours send inside
                                    the update pass, from a copy of x the library keeps (two more
-                                   arrays of the ring's size, library-owned); an iteration is then
-                                   two kernel launches instead of four                           */
+                                   arrays of the ring's size, library-owned).  If its norms are
+                                   accumulated by the update pass (norm_mode) and no tensor is
+                                   longer than 131 072 elements, evg_step is then ONE kernel launch:
+                                   the update pass runs the trigger tests itself.  evg_step_next
+                                   keeps the trigger kernel (two launches), and so does evg_step on
+                                   a ring once evg_step_next has been called on it               */
   evg_synth synth;
   /* DEVICE arenas owned by the caller, each P * evg_padded_numel() floats,
    * 16-byte aligned, non-overlapping, alive until evg_destroy.  Worker r's
@@ -175,7 +179,10 @@ typedef struct {
 /* Phases reported by evg_timing_read. */
 enum {
   EVG_PH_NORM = 0,       /* separate drift-norm pass (EVG_NORM_SEPARATE only)        */
-  EVG_PH_TRIGGER = 1,    /* norm finalisation, trigger test, thresholds, work lists  */
+  EVG_PH_TRIGGER = 1,    /* norm finalisation, trigger test, thresholds, work lists
+                            (no samples where the update pass runs the tests itself:
+                            cache-resident rings that send whole tensors, norms fused,
+                            no tensor above 131 072 elements, evg_step only)          */
   EVG_PH_SEND_FULL = 2,  /* whole-tensor copies into both mailboxes (no samples where
                             the receivers fetch the sends inside the update pass)     */
   EVG_PH_TOPK_SELECT = 3,/* threshold-key search for the Top-K set                   */

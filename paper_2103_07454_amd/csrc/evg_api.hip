@@ -79,6 +79,16 @@ struct evg_ctx {
   bool device_ahead = false;        // evg_step_next has been used: replays of a captured graph
                                     // advance the device's iteration without the host seeing
                                     // it, so iters / last_iter are re-read whenever needed
+  // Single-launch steps (cache-resident rings, whole-tensor sends, norms accumulated by the update
+  // pass, no tensor longer than 128 sweeps): the update pass runs the trigger tests itself.  What the
+  // tests read must then not be written in the same launch, so these arrays exist twice and a step
+  // writes the set it does not read; c->t always names the set that holds the current state.
+  struct SecondSet { double* partials; double* xhat_sq; float* delta; int32_t* last_event; };
+  // (the sums of squared xhat are not among them: such a ring's steps only read those)
+  SecondSet second{};
+  bool one_launch = false;          // the ring qualifies
+  bool replayable_used = false;     // evg_step_next has been called: a captured graph may hold the pointers
+                                    // of c->t, so the sets must not change places any more
   // evg_init_static: the tables are carved out of the device's static scratch block
   unsigned char* arena_base = nullptr;   // null = tables come from hipMalloc
   size_t arena_used = 0;
@@ -266,7 +276,7 @@ static uint32_t stage_num_for(uint32_t topk_ppm) {
 }
 
 static uint64_t table_bytes(uint64_t P, uint64_t L, uint64_t C, uint64_t SW, uint64_t hist_len, uint64_t Npad,
-                            uint64_t ktot, uint64_t stage_num, bool topk, bool norm_diff, bool pull) {
+                            uint64_t ktot, uint64_t stage_num, bool topk, bool norm_diff, bool pull, bool one_launch) {
   const uint64_t S = P * L, PC = P * C;
   uint64_t total = 0;
   auto add = [&total](uint64_t count, uint64_t elem) {
@@ -282,6 +292,10 @@ static uint64_t table_bytes(uint64_t P, uint64_t L, uint64_t C, uint64_t SW, uin
   add(4, 4); add(1, sizeof(IterState)); add(kDecayTable, 8);
   add(PC, 4);                                            // work_full
   if (pull) add(2 * P * Npad, 4);                        // xsnap
+  if (one_launch) {                                      // the second set of what the trigger tests read
+    add(PC * SW, 8); add(S, 4); add(S, 4);
+    if (norm_diff) add(S, 8);
+  }
   if (topk) {
     add(PC, 4); add(S * kHistBins, 4); add(S, 4); add(S, 4); add(PC, 8);
     const uint64_t stage = P * (Npad / 16 * stage_num);
@@ -420,6 +434,12 @@ static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_st
   t.stage_num = stage_num_for(cfg->topk_ppm);
   t.stage_stride = Npad / 16 * t.stage_num;
   t.x = cfg->x; t.xhat = cfg->xhat; t.mbox_l = cfg->mbox_l; t.mbox_r = cfg->mbox_r; t.vel = cfg->vel;
+  // one launch per iteration: the ring's receivers fetch the sends (see `pull` below), the update pass
+  // accumulates the norms, and one wavefront sums a tensor's sweep partials with two loads per lane
+  uint32_t most_sweeps = 0;
+  for (const LayerDesc& d : layers) most_sweeps = std::max(most_sweeps, d.nchunks * t.SW);
+  const bool one_launch = c->cached && !cfg->topk_ppm && !cfg->delivery_delay &&
+                          cfg->norm_mode == EVG_NORM_FUSED && most_sweeps <= 128;
   int dev = 0, cus = 256;
   ChunkDesc* d_chunks = nullptr;
   LayerDesc* d_layers = nullptr;
@@ -444,7 +464,7 @@ static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_st
   if (use_scratch) {
     const uint64_t need = table_bytes(P, L, C, t.SW, t.hist_len, Npad, ktot, t.stage_num, cfg->topk_ppm != 0,
                                       cfg->trigger_kind == EVG_TRIGGER_NORM_DIFF,
-                                      c->cached && !cfg->topk_ppm && !cfg->delivery_delay);
+                                      c->cached && !cfg->topk_ppm && !cfg->delivery_delay, one_launch);
     if (need > kScratchBytes) {
       evg_destroy(c);
       return fail(EVG_ERR_INVALID, "this configuration needs %llu bytes of tables; the static scratch block "
@@ -520,6 +540,16 @@ static evg_status init_common(evg_ctx** out, const evg_config* cfg, void* hip_st
   // itself from a copy of x it keeps (one more array of the ring's size, library-owned)
   const bool pull = c->cached && !cfg->topk_ppm && !cfg->delivery_delay;
   if (pull) TRY_OR_FREE(c->dalloc(&t.xsnap, 2 * (uint64_t)P * Npad, false));
+  if (one_launch) {
+    TRY_OR_FREE(c->dalloc(&c->second.partials, P * C * t.SW, true));
+    TRY_OR_FREE(c->dalloc(&c->second.delta, S, true));
+    TRY_OR_FREE(c->dalloc(&c->second.last_event, S, true));
+    if (cfg->trigger_kind == EVG_TRIGGER_NORM_DIFF) TRY_OR_FREE(c->dalloc(&c->second.xhat_sq, S, true));
+    c->one_launch = true;
+  }
+  // a step writes where it reads, unless it is a single-launch step (enqueue_step)
+  t.partials_out = t.partials; t.partials_hat_out = t.partials_hat; t.xhat_sq_out = t.xhat_sq;
+  t.delta_out = t.delta; t.last_event_out = t.last_event;
   if (cfg->topk_ppm) {
     TRY_OR_FREE(c->dalloc(&t.work_topk, P * C, true));
     TRY_OR_FREE(c->dalloc(&t.hist, S * kHistBins, true));
@@ -580,22 +610,33 @@ static evg_status refresh_iteration(evg_ctx* c) {
 }
 
 // The launch sequence of one iteration.  `timed`: bracket the phases with events.
-static evg_status enqueue_step(evg_ctx* c, const StepArgs& a, bool timed) {
+static evg_status enqueue_step(evg_ctx* c, const StepArgs& args, bool timed) {
   const evg_config& g = c->cfg;
-  const Tables& t = c->t;
+  Tables t = c->t;
+  StepArgs a = args;
   const bool fused = g.norm_mode == EVG_NORM_FUSED;
   const bool norm_diff = g.trigger_kind == EVG_TRIGGER_NORM_DIFF;
   const bool was_timing = c->timing;
   c->timing = was_timing && timed;
   struct Restore { evg_ctx* c; bool v; ~Restore() { c->timing = v; } } restore{c, was_timing};
   evg_status st;
+  // single launch: the update pass runs the trigger tests on the current set of arrays and writes
+  // the other set, which is the current one from then on.  Not once evg_step_next has been used:
+  // a captured graph holds c->t's pointers.
+  const bool single = c->one_launch && !c->replayable_used && !a.from_device;
+  if (single) {
+    a.one_launch = 1;
+    a.step_no = (uint32_t)c->iters;
+    t.partials_out = c->second.partials;
+    t.xhat_sq_out = c->second.xhat_sq; t.delta_out = c->second.delta; t.last_event_out = c->second.last_event;
+  }
   if (a.from_device) HIP_TRY(launch_begin(t, c->stream));
   if (!fused) {
     Phase ph(c, EVG_PH_NORM);
     HIP_TRY(launch_norm(t, norm_diff, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
   }
-  {
+  if (!single) {
     Phase ph(c, EVG_PH_TRIGGER);
     HIP_TRY(launch_trigger(t, a, c->stream));
     HIP_TRY(launch_scan(t, a, c->stream));
@@ -625,6 +666,14 @@ static evg_status enqueue_step(evg_ctx* c, const StepArgs& a, bool timed) {
     const int norm = !fused ? 0 : !norm_diff ? 1 : g.topk_ppm ? 3 : 2;
     HIP_TRY(launch_update(t, a, g.synth.dist, g.grad_mode, norm, c->stream));
     if ((st = ph.end()) != EVG_OK) return st;
+  }
+  if (single) {
+    Tables& ct = c->t;
+    std::swap(ct.partials, c->second.partials);
+    std::swap(ct.xhat_sq, c->second.xhat_sq); std::swap(ct.delta, c->second.delta);
+    std::swap(ct.last_event, c->second.last_event);
+    ct.partials_out = ct.partials; ct.partials_hat_out = ct.partials_hat; ct.xhat_sq_out = ct.xhat_sq;
+    ct.delta_out = ct.delta; ct.last_event_out = ct.last_event;
   }
   if (a.delay) {
     Phase ph(c, EVG_PH_DELIVER);
@@ -694,6 +743,7 @@ evg_status evg_step_next(evg_ctx* c, const float* grad) {
   evg_status st = fixed_args(c, grad, &a);
   if (st != EVG_OK) return st;
   a.from_device = 1;
+  c->replayable_used = true;
   if ((st = enqueue_step(c, a, false)) != EVG_OK) return st;
   c->device_ahead = true;
   return EVG_OK;

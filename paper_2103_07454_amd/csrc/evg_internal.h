@@ -57,6 +57,12 @@ struct Tables {
                            // tensors are sent (norm-difference trigger only)
   float* delta; float* last_norm; float* delta_before;
   int32_t* last_event;
+  // Where a step WRITES the sweep sums, and an event the threshold, its iteration and the squared
+  // norm of what was sent.  The same arrays as partials, partials_hat, delta, last_event, xhat_sq
+  // (which a step reads), except in a single-launch step, whose workgroups must all still see the
+  // values from before the step: there the two sets alternate from step to step.
+  double* partials_out; double* partials_hat_out; double* xhat_sq_out;
+  float* delta_out; int32_t* last_event_out;
   uint8_t* valid_l; uint8_t* valid_r; uint8_t* fired; uint8_t* near_tie;
   uint32_t* ev_full; uint32_t* ev_topk; uint32_t* near_cnt; uint32_t* nonfinite_cnt;
   float* slope_hist; uint32_t* slope_cnt;   // [S*hist_len], [S]
@@ -110,6 +116,8 @@ struct StepArgs {
   uint32_t xhat_reset;     // a Top-K event resets the whole tensor's xhat to x
   uint32_t cached;         // the arenas fit the last-level cache: ordinary instead of streaming accesses
   uint32_t pull;           // whole-tensor sends are fetched by the receivers inside the update pass
+  uint32_t one_launch;     // ... and the update pass also runs the trigger tests (no other kernel in the step)
+  uint32_t step_no;        // one_launch: steps completed before this one (picks the copy of x to read)
   uint32_t key0, key1;
   double decay_pow;        // decay^k
   float spike_prob, spike_gain;

@@ -7,85 +7,16 @@
 //   k_expand   writes the compact lists of chunks to copy / to Top-K select.
 //   k_copy     x -> left neighbour's right mailbox, right neighbour's left mailbox for
 //              every listed chunk: the stand-in for the one-sided puts of Section 6.
-#include "evg_device.h"
+#include "trigger_device.h"
 
 namespace evg {
 
 // The trigger test of one (worker, tensor), by one whole wavefront.
 __device__ __forceinline__ void trigger_segment(const Tables& T, const StepArgs& A, uint32_t seg) {
-  const uint32_t r = seg / T.L, l = seg % T.L;
-  const LayerDesc ld = T.layers[l];
-  const double* part = T.partials + ((size_t)r * T.C + ld.chunk0) * T.SW;
-  const uint32_t np = ld.nchunks * T.SW;
-  double acc = 0.0, acc_hat = 0.0;
-  for (uint32_t i = lane_id(); i < np; i += 64) acc += part[i];
-  acc = wave_sum(acc);
-  // norm-difference trigger: the squared norm of xhat comes from the arena sums, or, where
-  // whole tensors are sent, from the scalar kept at the tensor's last event
-  const bool hat_sums = A.norm_src == 2 || (A.norm_src == 1 && T.last_event[seg] < 0);
-  if (hat_sums) {
-    const double* ph = T.partials_hat + ((size_t)r * T.C + ld.chunk0) * T.SW;
-    for (uint32_t i = lane_id(); i < np; i += 64) acc_hat += ph[i];
-    acc_hat = wave_sum(acc_hat);
-  }
-  if (lane_id() != 0) return;
-
-  const uint32_t k = step_k(T, A);
-  float d;
-  if (A.norm_src == 0) {
-    d = (float)sqrt(acc);
-  } else {
-    if (!hat_sums) acc_hat = T.xhat_sq[seg];
-    d = __builtin_fabsf((float)sqrt(acc) - (float)sqrt(acc_hat));
-  }
-  const float dl = T.delta[seg];
-  T.last_norm[seg] = d;
-  T.delta_before[seg] = dl;
-  if (!(__builtin_fabsf(d) <= 3.402823466e+38f)) T.nonfinite_cnt[seg] += 1;   // NaN or inf
-  const bool near = __builtin_fabsf(d - dl) < 1e-6f * dl;
-  T.near_tie[seg] = near ? 1 : 0;
-  if (near) T.near_cnt[seg] += 1;
-  const bool fire = (A.force_first && k == 0) || (d >= dl);   // NaN never fires
-  uint8_t code = 0;
-  if (fire) {
-    const int32_t khat = T.last_event[seg];
-    if (A.thr_mode == 1) {
-      const float slope = d / (float)((int32_t)k - khat);
-      if (T.hist_len <= 1) {
-        T.delta[seg] = A.horizon * slope;
-      } else {
-        // mean of the slopes between the last hist_len consecutive events (Section 7)
-        float* hs = T.slope_hist + (size_t)seg * T.hist_len;
-        uint32_t cnt = T.slope_cnt[seg];
-        if (cnt == T.hist_len) {
-          for (uint32_t i = 1; i < cnt; ++i) hs[i - 1] = hs[i];
-          cnt -= 1;
-        }
-        hs[cnt++] = slope;
-        T.slope_cnt[seg] = cnt;
-        float sum = 0.0f;
-        for (uint32_t i = 0; i < cnt; ++i) sum += hs[i];
-        T.delta[seg] = A.horizon * (sum / (float)cnt);
-      }
-    }
-    T.last_event[seg] = (int32_t)k;
-    if (A.norm_src == 1) T.xhat_sq[seg] = acc;    // the whole tensor is sent: xhat becomes x
-    // a tensor's first message has nothing to patch on the receiving side: send it whole
-    if (!A.topk_on || khat < 0) { code = 1; T.ev_full[seg] += 1; }
-    else { code = 2; T.ev_topk[seg] += 1; }
-    const uint32_t left = (r + T.P - 1) % T.P, right = (r + 1) % T.P;
-    if (!A.delay) {                     // otherwise set when the put lands (k_deliver)
-      T.valid_r[left * T.L + l] = 1;    // I am my left neighbour's right-hand source
-      T.valid_l[right * T.L + l] = 1;
-    }
-  }
-  T.fired[seg] = code;
-}
-
-// The step's bookkeeping (normally the scan kernel's first thread does it).
-__device__ __forceinline__ void close_step(const Tables& T, const StepArgs& A) {
-  T.it->k_next = step_k(T, A) + 1;
-  T.it->iters += 1;
+  double acc, acc_hat;
+  bool hat_sums;
+  segment_sums(T, A, seg, &acc, &acc_hat, &hat_sums);
+  if (lane_id() == 0) (void)segment_test<true, true>(T, A, seg, acc, acc_hat, hat_sums);
 }
 
 __global__ __launch_bounds__(kThreads) void k_trigger(Tables T, StepArgs A) {

@@ -14,7 +14,7 @@
 // (the receiving end of the put, Section 6).  A message slice is scattered into an
 // LDS window first, so that global accesses stay 16-byte wide and coalesced, and a
 // float4 is written back only if its 64-byte group changed.
-#include "evg_device.h"
+#include "trigger_device.h"
 
 // Build-time variants of the Top-K message handling, kept so that the measurements behind the
 // defaults can be repeated (EVG_EXTRA_FLAGS="-DEVG_PATCH_WINDOWS=2" python -m paper_2103_07454_amd.build):
@@ -70,10 +70,10 @@ __global__ __launch_bounds__(kThreads) void k_norm(Tables T) {
   }
   const size_t slot = ((size_t)r * T.C + c) * T.SW + sub;
   const double total = block_sum(acc, ws);
-  if (threadIdx.x == 0) T.partials[slot] = total;
+  if (threadIdx.x == 0) T.partials_out[slot] = total;
   if (NORMDIFF) {
     const double total_hat = block_sum(acc_hat, ws);
-    if (threadIdx.x == 0) T.partials_hat[slot] = total_hat;
+    if (threadIdx.x == 0) T.partials_hat_out[slot] = total_hat;
   }
 }
 
@@ -155,9 +155,18 @@ __device__ __forceinline__ void block_sums(const double v[SPW], double* ws, doub
 // mailbox here; and the new x is also written to the other of the two copies for the next
 // iteration (two copies in turn: the one read now is written by nobody in this launch).  Fewer
 // launches per iteration for rings that live in the cache, where launches are what costs.
-template <int DIST, bool GRADBUF, int NORM, bool TOPK, bool HISTA, int SPW, bool STREAM, bool PULL = false>
+// TESTS (with PULL): no kernel has run the trigger tests of this iteration.  Every workgroup
+// runs the three it depends on itself (its own tensor's and that tensor's of the two
+// neighbours: three wavefronts, one each, from the sweep sums the previous pass left), and the
+// first workgroup of each tensor books its tensor's outcome.  What the tests read is not
+// written by this launch (Tables: the _out arrays), so every workgroup decides alike.  One
+// launch per iteration.
+template <int DIST, bool GRADBUF, int NORM, bool TOPK, bool HISTA, int SPW, bool STREAM, bool PULL = false,
+          bool TESTS = false>
 __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
+  static_assert(!TESTS || (PULL && !TOPK && SPW == 1), "the tests ride in the pass of rings whose receivers fetch the sends");
   __shared__ double ws[4 * SPW];
+  __shared__ uint32_t outcome[3];
   // LDS: the windows of the three patches; once those are consumed the same
   // storage holds the key histogram
   constexpr int NWIN = EVG_PATCH_WINDOWS;
@@ -172,19 +181,49 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
   const uint32_t c = blockIdx.x / groups, sub0 = (blockIdx.x % groups) * SPW, r = blockIdx.y;
   const ChunkDesc cd = T.chunks[c];
   const uint32_t seg = r * T.L + cd.layer;
-  const bool vl = T.valid_l[seg] != 0, vr = T.valid_r[seg] != 0;
-  // PULL: did my neighbours send this tensor whole in this iteration? (then vl / vr are set)
+  bool vl = T.valid_l[seg] != 0, vr = T.valid_r[seg] != 0;
   const uint32_t lw = (r + T.P - 1) % T.P, rw = (r + 1) % T.P;
-  const bool from_l = PULL && T.fired[lw * T.L + cd.layer] == 1;
-  const bool from_r = PULL && T.fired[rw * T.L + cd.layer] == 1;
-  // the trigger kernel has counted this step already: step n reads copy (n-1) & 1, writes copy n & 1
+  uint32_t my_event;
+  bool from_l = false, from_r = false;
+  if (TESTS) {
+    const uint32_t segs[3] = {seg, lw * T.L + cd.layer, rw * T.L + cd.layer};
+    const bool books = blockIdx.x == T.layers[cd.layer].chunk0 * groups;    // the tensor's first workgroup
+    if (wave_id() < 3) {
+      const uint32_t sg = segs[wave_id()];
+      double acc, acc_hat;
+      bool hat_sums;
+      segment_sums(T, A, sg, &acc, &acc_hat, &hat_sums);
+      if (lane_id() == 0)
+        outcome[wave_id()] = (books && wave_id() == 0) ? segment_test<true, false>(T, A, sg, acc, acc_hat, hat_sums)
+                                                       : segment_test<false, false>(T, A, sg, acc, acc_hat, hat_sums);
+    }
+    __syncthreads();
+    my_event = outcome[0];
+    from_l = outcome[1] == 1;
+    from_r = outcome[2] == 1;
+    // a neighbour's send fills my mailbox slot for good (the flags only ever go from 0 to 1, so
+    // a workgroup that reads one after the booking below sees what it would have computed)
+    vl = vl || from_l;
+    vr = vr || from_r;
+    if (books && threadIdx.x == 0) {
+      if (from_l) T.valid_l[seg] = 1;
+      if (from_r) T.valid_r[seg] = 1;
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) close_step(T, A);
+  } else {
+    my_event = T.fired[seg];
+    // PULL: did my neighbours send this tensor whole in this iteration? (then vl / vr are set)
+    from_l = PULL && T.fired[lw * T.L + cd.layer] == 1;
+    from_r = PULL && T.fired[rw * T.L + cd.layer] == 1;
+  }
+  // step n reads copy (n-1) & 1 of x and writes copy n & 1; where a kernel ahead of this one ran
+  // the tests it has counted this step already
   const size_t arena = (size_t)T.P * T.Npad;
-  const uint64_t step_no = PULL ? T.it->iters : 0;
+  const uint64_t step_no = !PULL ? 0 : TESTS ? (uint64_t)A.step_no + 1 : T.it->iters;
   const float* snap_in = PULL ? T.xsnap + ((step_no + 1) & 1) * arena : nullptr;
   float* snap_out = PULL ? T.xsnap + (step_no & 1) * arena : nullptr;
   // xhat := x for the whole tensor: after a whole send, or after any event when a Top-K
   // event is read as resetting the tensor's xhat
-  const uint32_t my_event = T.fired[seg];
   const bool sent_whole = my_event == 1 || (TOPK && A.xhat_reset && my_event == 2);
   const size_t base = (size_t)r * T.Npad + cd.off;
   const float third = 0.333333343f;   // (float)(1/3): the ring's mixing weight
@@ -369,13 +408,13 @@ __global__ __launch_bounds__(kThreads) void k_update(Tables T, StepArgs A) {
     block_sums<SPW>(acc, ws, total);
     if (threadIdx.x == 0) {
 #pragma unroll
-      for (int u = 0; u < SPW; ++u) T.partials[slot + u] = total[u];
+      for (int u = 0; u < SPW; ++u) T.partials_out[slot + u] = total[u];
     }
     if (NORM == 3) {
       block_sums<SPW>(acc_hat, ws, total);
       if (threadIdx.x == 0) {
 #pragma unroll
-        for (int u = 0; u < SPW; ++u) T.partials_hat[slot + u] = total[u];
+        for (int u = 0; u < SPW; ++u) T.partials_hat_out[slot + u] = total[u];
       }
     }
   }
@@ -407,6 +446,13 @@ static void launch_update_w(const Tables& t, const StepArgs& a, uint32_t dist, u
   const dim3 grid(t.C * (t.SW / SPW), t.P), block(kThreads);
   if (!TOPK && a.pull) {     // the host sets pull only for cache-resident rings with whole-tensor sends
     constexpr bool NT = false, NH = false;
+    if (a.one_launch) {      // ... and one_launch only where the pass accumulates the norms (NORM != 0)
+      constexpr bool TS = NORM != 0;
+      if (grad_mode == 1) k_update<0, true, NORM, NT, NH, 1, false, true, TS><<<grid, block, 0, s>>>(t, a);
+      else if (dist == 0) k_update<0, false, NORM, NT, NH, 1, false, true, TS><<<grid, block, 0, s>>>(t, a);
+      else k_update<1, false, NORM, NT, NH, 1, false, true, TS><<<grid, block, 0, s>>>(t, a);
+      return;
+    }
     if (grad_mode == 1) k_update<0, true, NORM, NT, NH, 1, false, true><<<grid, block, 0, s>>>(t, a);
     else if (dist == 0) k_update<0, false, NORM, NT, NH, 1, false, true><<<grid, block, 0, s>>>(t, a);
     else k_update<1, false, NORM, NT, NH, 1, false, true><<<grid, block, 0, s>>>(t, a);
