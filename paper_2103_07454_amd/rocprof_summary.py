@@ -114,6 +114,11 @@ def main():
               "fraction_fired_full": b["config"]["fraction_fired_full"], "kernels": {}}
 
     # ---- HBM traffic --------------------------------------------------------------------
+    if a.fetch and a.write and not any("k_copy" in k for k in counter_rows(a.fetch, "FETCH_SIZE")):
+        # cache-resident rings that send whole tensors never launch the copy kernel, and their
+        # counters would mostly show cache hits anyway
+        print(f"no k_copy launch in {a.fetch}: the counters cannot be calibrated, no traffic summary is written")
+        a.fetch = a.write = None
     if a.fetch and a.write:
         fetch, write = counter_rows(a.fetch, "FETCH_SIZE"), counter_rows(a.write, "WRITE_SIZE")
         npad4 = sum((int(n) + 3) // 4 * 4 for n in w.layer_numel)
@@ -197,9 +202,10 @@ def main():
                     f"{rf['avg_launch_ms']:.2f} ms per launch."]
         with open(os.path.join(a.out, f"sq_counters_{w.name}.md"), "w") as f:
             f.write("\n".join(out) + "\n")
-    with open(os.path.join(a.out, f"counters_{w.name}.json"), "w") as f:
-        json.dump(record, f, indent=1, sort_keys=True)
-        f.write("\n")
+    if record["kernels"]:                  # nothing to record from a kernel trace alone
+        with open(os.path.join(a.out, f"counters_{w.name}.json"), "w") as f:
+            json.dump(record, f, indent=1, sort_keys=True)
+            f.write("\n")
     print(f"wrote summaries of {w.name} under {a.out}/")
 
 
